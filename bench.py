@@ -1,0 +1,154 @@
+"""Benchmark of the fused Signum step on the ResNet-50-sized workload (d = 25,557,032, M = 15).
+
+A step is one pass of the whole hot path -- momentum, sign, majority vote, parameter update -- for
+all M simulated workers: one call of ssv_signum_step on gradients that are already resident in HBM.
+Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+BYTES_PER_COORD = 15 * 12 + 8  # per coordinate: M x (read g, read v, write v) fp32 + read/write x fp32
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workers", type=int, default=15)
+    ap.add_argument("--d", type=int, default=25_557_032)
+    ap.add_argument("--row-align", type=int, default=1,
+                    help="round row strides up to a multiple of this many elements")
+    ap.add_argument("--grad-sets", type=int, default=8, help="distinct pre-generated gradient sets that are cycled")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 22, help="coordinates in the oracle's timed sample")
+    return ap.parse_args()
+
+
+def read_traffic(name):
+    """Measured HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", name)
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("hbm_bytes_per_launch"):
+                    return float(line.split()[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU (the M workers are M buffers on that GPU); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import paper_1810_05291_amd as sv
+    import workloads as wl
+
+    if not os.path.exists(sv.library_path()):
+        from paper_1810_05291_amd import build as hip_build
+        hip_build.build()
+    sv.load_library()
+    dev = "cuda:0"
+    M, d, K, Wm = args.workers, args.d, args.steps, args.warmup
+    beta, lr = 0.9, 1e-4
+    stride = ((d + args.row_align - 1) // args.row_align) * args.row_align
+
+    # ---- inputs resident in HBM before the timed region ---------------------------------------
+    mu = wl.shared_mean(d, seed=1, device=dev)
+    x = wl.gaussian((d,), 0.02, seed=2, device=dev)
+    v = torch.zeros((M, stride), device=dev)[:, :d]
+    nsets = max(1, min(args.grad_sets, K + Wm))
+    grads = [wl.worker_gradients(mu, M, s, base_seed=1000, row_stride=stride) for s in range(nsets)]
+    torch.cuda.synchronize()
+
+    # ---- CPU oracle on a bounded sample of the same workload (also a parity check of the warmup) ----
+    ds = min(args.cpu_sample, d)
+    cpu = None
+    x_ref = v_ref = None
+    if not args.no_cpu_baseline:
+        import oracle as ora
+        x_ref = wl.to_numpy(x[:ds]).copy()
+        v_ref = np.zeros((M, ds), np.float32)
+        g_h = [np.ascontiguousarray(wl.to_numpy(grads[s % nsets][:, :ds].contiguous())) for s in range(min(Wm, nsets))]
+        t_cpu, n_cpu = 0.0, 0
+        for s in range(Wm):
+            t0 = time.perf_counter()
+            ora.signum_step(g_h[s % len(g_h)], v_ref, beta, x_ref, lr)
+            t_cpu += time.perf_counter() - t0
+            n_cpu += 1
+        # keep timing (on copies, so the parity state is not disturbed) until about 10 s of CPU work
+        xs, vs = x_ref.copy(), v_ref.copy()
+        while t_cpu < 10.0 and n_cpu < 200:
+            t0 = time.perf_counter()
+            ora.signum_step(g_h[n_cpu % len(g_h)], vs, beta, xs, lr)
+            t_cpu += time.perf_counter() - t0
+            n_cpu += 1
+        cpu = {"value": M * ds * n_cpu / t_cpu, "unit": "worker-coordinates/s (M*d/s)", "cores": ora.max_threads(),
+               "kind": "oracle",
+               "sample": f"first {ds} of {d} coordinates, M={M}, {n_cpu} fused steps, {t_cpu:.1f} s of CPU time"}
+
+    # ---- warmup (untimed) ------------------------------------------------------------------------
+    for s in range(Wm):
+        sv.signum_step(grads[s % nsets], v, beta, x, lr)
+    torch.cuda.synchronize()
+    parity = None
+    if x_ref is not None and Wm <= nsets:
+        ok = np.array_equal(wl.to_numpy(x[:ds]), x_ref) and \
+            np.array_equal(wl.to_numpy(v[:, :ds].contiguous()), v_ref)
+        parity = "bit-exact vs oracle on the sample after warmup" if ok else "MISMATCH vs oracle"
+
+    # ---- timed region: exactly K steps ---------------------------------------------------------------
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record()                       # on the current stream, the one the library launches on
+    for s in range(K):
+        sv.signum_step(grads[(Wm + s) % nsets], v, beta, x, lr)
+    ev1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    wall_ms = (t1 - t0) * 1e3 / K
+    kern_ms = ev0.elapsed_time(ev1) / K
+
+    algo_bytes = float(M * 12 + 8) * d
+    achieved = algo_bytes / (kern_ms * 1e-3) / 1e9
+    out = {
+        "metric": "voted coords/sec (M*d/s), fused Signum step (momentum + sign + majority vote + update)",
+        "value": M * d / (wall_ms * 1e-3),
+        "unit": "worker-coordinates/s (M*d/s)",
+        "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": wall_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "resnet50-sized fused Signum step", "d": d, "M": M, "beta": beta, "lr": lr,
+                   "grad_dtype": "f32", "weight_dtype": "f32", "row_stride": stride,
+                   "gradient_sets_cycled": nsets, "kernel": "ssv_signum_step"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": read_traffic("signum_step_resnet50_pmc.txt"),
+                     "kernel_ms": kern_ms, "algorithmic_bytes_per_launch": algo_bytes},
+        "cpu_baseline": cpu,
+        "parity": parity,
+    }
+    print(json.dumps(out), flush=True)
+    if parity is not None and parity.startswith("MISMATCH"):
+        sys.exit(1)
+
+
+if __name__ == "__main__":
+    main()

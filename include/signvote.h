@@ -1,0 +1,137 @@
+/*
+ * signvote.h -- C ABI of libsignvote: the data-parallel hot path of signSGD / Signum with
+ * majority vote (arXiv 1810.05291, Algorithm 1) on one AMD MI355X (gfx950).
+ *
+ * The M workers of Algorithm 1 are M rows of caller-owned device buffers on one GPU:
+ *     on worker m :  v_m <- (1 - beta) g_m + beta v_m ;  transmit sign(v_m) as 1 bit/coordinate
+ *     on server   :  V <- sum_m sign(v_m) ;  transmit sign(V)
+ *     everywhere  :  x <- x - eta (sign(V) + lambda x)
+ * All operations are element-wise over the d coordinates.
+ *
+ * Conventions (the paper does not fix them; they are this library's stated readings):
+ *   - sign(0) = +1: the transmitted bit is (value >= 0) under IEEE comparison, so +0 and -0 give
+ *     bit 1, NaN gives bit 0, +-Inf give 1 / 0.
+ *   - vote ties (even M, V = 0) give +1: vote bit = [#(bits set) >= (M + 1) / 2].
+ *   - packed format: uint64 words, coordinate 64 w + i is bit i of word w (bit 0 = least
+ *     significant), bit 1 <-> +1, bit 0 <-> -1.  A row of d coordinates has ceil(d / 64) words.
+ *     Producers write the padding bits of the last word as 0; consumers ignore them.
+ *   - fp32 arithmetic order: v <- fma(beta, v, (1 - beta) * g), (1 - beta) rounded once to fp32;
+ *     x <- x + (-eta | +eta) when lambda == 0, else t = fma(lambda, x, s), x <- fma(-eta, t, x).
+ *     bf16 values are widened to fp32 (exact), results rounded to nearest even.
+ *
+ * Memory and ownership: every pointer is DEVICE memory owned by the caller unless the argument
+ * is documented as host memory.  The library allocates nothing, keeps no state between calls and
+ * never frees.  Matrices are row-major, one row per worker, with the row stride given in
+ * elements (or in 64-bit words for packed rows).  Inputs must not overlap outputs.  v and x are
+ * updated in place.
+ *
+ * Execution: `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ * enqueue kernels and return; the caller synchronises.  Calls on one stream run in order.
+ *
+ * Errors: every function returns SSV_OK (0) or a negative ssv_status.  Argument errors are
+ * detected before anything is launched and leave all buffers untouched.  Nothing is printed,
+ * nothing aborts.
+ *
+ * Alignment: base pointers of fp32 / bf16 / packed buffers must be aligned to their element size
+ * (4 / 2 / 8 bytes), else SSV_ERR_ALIGN.  Fastest paths need 16-byte aligned bases and row
+ * strides that are multiples of 16 bytes; other shapes take a narrower-load path with the same
+ * results.
+ */
+#ifndef SIGNVOTE_H
+#define SIGNVOTE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SSV_MAX_WORKERS 1023            /* 1 <= M <= SSV_MAX_WORKERS */
+#define SSV_MAX_COORDS (1LL << 40)      /* 1 <= d <= SSV_MAX_COORDS  */
+
+typedef enum { SSV_F32 = 0, SSV_BF16 = 1 } ssv_dtype;
+
+typedef enum {
+    SSV_OK = 0,
+    SSV_ERR_NULL = -1,   /* a required pointer is NULL */
+    SSV_ERR_SHAPE = -2,  /* d < 1, d > SSV_MAX_COORDS, M < 1, M > SSV_MAX_WORKERS, row stride < row length */
+    SSV_ERR_ALIGN = -3,  /* a base pointer is not aligned to its element size */
+    SSV_ERR_DTYPE = -4,  /* dtype is not SSV_F32 / SSV_BF16 */
+    SSV_ERR_PARAM = -5,  /* beta outside [0, 1), lr or weight_decay not finite, momentum asked without v */
+    SSV_ERR_HIP = -6     /* the HIP runtime refused the launch */
+} ssv_status;
+
+/*
+ * Sign compression (Algorithm 1, "push sign(v_m)"; Section 4, bit-packing of sign tensors).
+ * For each of the M rows of x:  signs[m][w] bit i = (x[m][64 w + i] >= 0).
+ *   x      device, M rows of d elements of type dt, row stride x_row_stride elements (>= d)
+ *   signs  device, M rows of ceil(d/64) uint64 words, row stride signs_row_stride_words (>= ceil(d/64))
+ */
+int ssv_sign_pack(const void* x, int dt, int M, int64_t d, int64_t x_row_stride,
+                  uint64_t* signs, int64_t signs_row_stride_words, void* stream);
+
+/*
+ * Worker side of Signum (Algorithm 1, "update momentum" then "push sign(v_m)").
+ * v[m] <- (1 - beta) g[m] + beta v[m] in place (fp32), signs[m] = packed (v[m] >= 0).
+ *   g      device, M rows of d elements of type g_dt, row stride g_row_stride
+ *   v      device, M rows of d fp32, row stride v_row_stride, read and written
+ *   beta   in [0, 1)
+ */
+int ssv_signum_momentum_pack(const void* g, int g_dt, float* v, int M, int64_t d,
+                             int64_t g_row_stride, int64_t v_row_stride, float beta,
+                             uint64_t* signs, int64_t signs_row_stride_words, void* stream);
+
+/*
+ * Server side (Algorithm 1, "aggregate sign momenta" and "broadcast majority vote"):
+ * vote[w] bit i = [ #{m : signs[m][w] bit i set} >= (M + 1) / 2 ], i.e. sign(sum_m +-1) with
+ * ties to +1.  Padding bits of the inputs are ignored; those of `vote` are written 0.
+ *   signs  device, M packed rows;  vote  device, ceil(d/64) words
+ */
+int ssv_majority_vote(const uint64_t* signs, int M, int64_t d, int64_t signs_row_stride_words,
+                      uint64_t* vote, void* stream);
+
+/*
+ * Parameter update (Algorithm 1, "update parameters"): x <- x - lr (s + weight_decay x), s = +1
+ * where the vote bit is set, else -1.  In place on x (d elements of type x_dt).
+ */
+int ssv_apply_sign_update(void* x, int x_dt, int64_t d, const uint64_t* vote,
+                          float lr, float weight_decay, void* stream);
+
+/*
+ * Fused server + update: ssv_majority_vote followed by ssv_apply_sign_update in one kernel; the
+ * vote never makes a round trip through memory.  vote_out may be NULL; when given it receives
+ * the packed vote.
+ */
+int ssv_vote_apply(const uint64_t* signs, int M, int64_t d, int64_t signs_row_stride_words,
+                   void* x, int x_dt, float lr, float weight_decay, uint64_t* vote_out,
+                   void* stream);
+
+/*
+ * One whole iteration of Algorithm 1 for all M workers in one kernel: momentum, sign, vote and
+ * update; signs and vote counts stay in registers.
+ *   v == NULL    signSGD ("Setting beta = 0 yields signSGD"): no momentum state is read or
+ *                written and the sign is taken of g itself; beta must then be 0.
+ *   v != NULL    Signum: v is updated in place as in ssv_signum_momentum_pack.
+ *   vote_out     optional, ceil(d/64) words: the packed vote.
+ *   signs_out    optional, M packed rows (stride signs_row_stride_words): what each worker
+ *                transmitted (after worker_flip).
+ *   worker_flip  optional, HOST memory, M bytes: nonzero = that worker transmits the negation of
+ *                its sign vector (the sign-inverting adversary of Definition 1 / Section 4.1).
+ *                Its momentum stays honest.  Read before the call returns.
+ */
+int ssv_signum_step(const void* g, int g_dt, float* v, int M, int64_t d,
+                    int64_t g_row_stride, int64_t v_row_stride, float beta,
+                    void* x, int x_dt, float lr, float weight_decay,
+                    uint64_t* vote_out, uint64_t* signs_out, int64_t signs_row_stride_words,
+                    const uint8_t* worker_flip, void* stream);
+
+/* Static, NUL-terminated description of a status code (host memory, never freed). */
+const char* ssv_status_string(int status);
+
+/* Library version: major * 1000 + minor. */
+int ssv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SIGNVOTE_H */

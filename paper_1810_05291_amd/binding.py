@@ -1,0 +1,201 @@
+"""ctypes binding of libsignvote.so: same names as the C ABI, argument marshalling only.
+
+Tensors must live on the GPU.  Packed sign rows are torch.int64 tensors (bit patterns of the
+uint64 words).  Every call is enqueued on torch's current stream of the tensors' device and
+returns without synchronising.
+"""
+import ctypes
+import os
+
+import torch
+
+SSV_F32 = 0
+SSV_BF16 = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+_c_i64 = ctypes.c_int64
+_c_int = ctypes.c_int
+_c_f = ctypes.c_float
+_c_p = ctypes.c_void_p
+
+_SIGNATURES = {
+    "ssv_sign_pack": [_c_p, _c_int, _c_int, _c_i64, _c_i64, _c_p, _c_i64, _c_p],
+    "ssv_signum_momentum_pack": [_c_p, _c_int, _c_p, _c_int, _c_i64, _c_i64, _c_i64, _c_f, _c_p, _c_i64, _c_p],
+    "ssv_majority_vote": [_c_p, _c_int, _c_i64, _c_i64, _c_p, _c_p],
+    "ssv_apply_sign_update": [_c_p, _c_int, _c_i64, _c_p, _c_f, _c_f, _c_p],
+    "ssv_vote_apply": [_c_p, _c_int, _c_i64, _c_i64, _c_p, _c_int, _c_f, _c_f, _c_p, _c_p],
+    "ssv_signum_step": [_c_p, _c_int, _c_p, _c_int, _c_i64, _c_i64, _c_i64, _c_f, _c_p, _c_int, _c_f, _c_f,
+                        _c_p, _c_p, _c_i64, _c_p, _c_p],
+}
+
+
+class SignvoteError(RuntimeError):
+    def __init__(self, name, status):
+        self.status = int(status)
+        super().__init__(f"{name} failed with status {status}: {status_string(status)}")
+
+
+def library_path() -> str:
+    return os.environ.get("SIGNVOTE_LIB", os.path.join(_HERE, "libsignvote.so"))
+
+
+def load_library():
+    """Load libsignvote.so (built in-tree).  Raises ImportError if it is missing: there is no fallback."""
+    global _LIB
+    if _LIB is None:
+        path = library_path()
+        if not os.path.exists(path):
+            raise ImportError(f"{path} not found: build it with `python -m paper_1810_05291_amd.build`")
+        lib = ctypes.CDLL(path)
+        for name, argtypes in _SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.argtypes = argtypes
+            fn.restype = _c_int
+        lib.ssv_status_string.argtypes = [_c_int]
+        lib.ssv_status_string.restype = ctypes.c_char_p
+        lib.ssv_version.argtypes = []
+        lib.ssv_version.restype = _c_int
+        _LIB = lib
+    return _LIB
+
+
+def status_string(status: int) -> str:
+    return load_library().ssv_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(load_library().ssv_version())
+
+
+def words_for(d: int) -> int:
+    return (int(d) + 63) // 64
+
+
+def _dt(t):
+    if t.dtype == torch.float32:
+        return SSV_F32
+    if t.dtype == torch.bfloat16:
+        return SSV_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _dev(*tensors):
+    dev = None
+    for t in tensors:
+        if t is None:
+            continue
+        if not t.is_cuda:
+            raise ValueError("libsignvote works on GPU memory only")
+        if dev is None:
+            dev = t.device
+        elif t.device != dev:
+            raise ValueError("all tensors must be on one device")
+    return dev
+
+
+def _rows(t):
+    """(M, d, row stride in elements) of a 2-D tensor whose rows are contiguous."""
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError("expected a 2-D tensor with contiguous rows")
+    return t.shape[0], t.shape[1], (t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1]))
+
+
+def _vec(t):
+    if t.dim() != 1 or (t.numel() > 1 and t.stride(0) != 1):
+        raise ValueError("expected a contiguous 1-D tensor")
+    return t
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream(dev):
+    return torch.cuda.current_stream(dev).cuda_stream
+
+
+def _check(name, rc):
+    if rc != 0:
+        raise SignvoteError(name, rc)
+
+
+def sign_pack(x, signs=None):
+    """signs[m] = packed (x[m] >= 0) for every row of the 2-D tensor x."""
+    M, d, xs = _rows(x)
+    dev = _dev(x, signs)
+    if signs is None:
+        signs = torch.empty((M, words_for(d)), dtype=torch.int64, device=dev)
+    _, _, ss = _rows(signs)
+    _check("ssv_sign_pack", load_library().ssv_sign_pack(_ptr(x), _dt(x), M, d, xs, _ptr(signs), ss, _stream(dev)))
+    return signs
+
+
+def signum_momentum_pack(g, v, beta, signs=None):
+    """v <- (1-beta) g + beta v in place; returns packed signs of the new v."""
+    M, d, gs = _rows(g)
+    Mv, dv, vs = _rows(v)
+    if (Mv, dv) != (M, d) or v.dtype != torch.float32:
+        raise ValueError("v must be fp32 with the shape of g")
+    dev = _dev(g, v, signs)
+    if signs is None:
+        signs = torch.empty((M, words_for(d)), dtype=torch.int64, device=dev)
+    _, _, ss = _rows(signs)
+    _check("ssv_signum_momentum_pack",
+           load_library().ssv_signum_momentum_pack(_ptr(g), _dt(g), _ptr(v), M, d, gs, vs, float(beta), _ptr(signs),
+                                                   ss, _stream(dev)))
+    return signs
+
+
+def majority_vote(signs, d, vote=None):
+    """Packed element-wise majority over the rows of `signs` (ties -> +1)."""
+    M, _, ss = _rows(signs)
+    dev = _dev(signs, vote)
+    if vote is None:
+        vote = torch.empty((words_for(d),), dtype=torch.int64, device=dev)
+    _check("ssv_majority_vote", load_library().ssv_majority_vote(_ptr(signs), M, d, ss, _ptr(_vec(vote)), _stream(dev)))
+    return vote
+
+
+def apply_sign_update(x, vote, lr, weight_decay=0.0):
+    """x <- x - lr (vote + weight_decay x) in place."""
+    dev = _dev(x, vote)
+    _check("ssv_apply_sign_update",
+           load_library().ssv_apply_sign_update(_ptr(_vec(x)), _dt(x), x.numel(), _ptr(_vec(vote)), float(lr),
+                                                float(weight_decay), _stream(dev)))
+    return x
+
+
+def vote_apply(signs, d, x, lr, weight_decay=0.0, vote_out=None):
+    """Fused majority vote + update from packed rows."""
+    M, _, ss = _rows(signs)
+    dev = _dev(signs, x, vote_out)
+    _check("ssv_vote_apply",
+           load_library().ssv_vote_apply(_ptr(signs), M, d, ss, _ptr(_vec(x)), _dt(x), float(lr), float(weight_decay),
+                                         _ptr(vote_out), _stream(dev)))
+    return x
+
+
+def signum_step(g, v, beta, x, lr, weight_decay=0.0, vote_out=None, signs_out=None, worker_flip=None):
+    """One fused iteration of Algorithm 1 for all workers.  v may be None (signSGD, beta = 0)."""
+    M, d, gs = _rows(g)
+    vs = 0
+    if v is not None:
+        Mv, dv, vs = _rows(v)
+        if (Mv, dv) != (M, d) or v.dtype != torch.float32:
+            raise ValueError("v must be fp32 with the shape of g")
+    if _vec(x).numel() != d:
+        raise ValueError("x must have d elements")
+    dev = _dev(g, v, x, vote_out, signs_out)
+    ss = 0
+    if signs_out is not None:
+        _, _, ss = _rows(signs_out)
+    flip = None
+    if worker_flip is not None:
+        flip = (ctypes.c_uint8 * M)(*[1 if f else 0 for f in worker_flip])
+    _check("ssv_signum_step",
+           load_library().ssv_signum_step(_ptr(g), _dt(g), _ptr(v), M, d, gs, vs, float(beta), _ptr(x), _dt(x),
+                                          float(lr), float(weight_decay), _ptr(vote_out), _ptr(signs_out), ss,
+                                          ctypes.cast(flip, _c_p) if flip is not None else None, _stream(dev)))
+    return x

@@ -1,0 +1,159 @@
+// The C ABI of libsignvote (declared in include/signvote.h): argument validation, choice of the
+// load-width path from pointer/stride alignment, and kernel dispatch.  No allocation, no state.
+#include <cmath>
+#include <cstdlib>
+
+#include "../../include/signvote.h"
+#include "common.h"
+
+namespace ssv {
+
+static int env_int(const char* name) {
+    const char* s = std::getenv(name);
+    return s ? std::atoi(s) : 0;
+}
+
+const Tuning& tuning() {
+    static const Tuning t = {env_int("SSV_TUNE_STEP_TILES_PER_WAVE"), env_int("SSV_TUNE_VOTE_TILES_PER_WAVE"),
+                             env_int("SSV_TUNE_XCD_REMAP")};
+    return t;
+}
+
+static inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+static inline int64_t words_for(int64_t d) { return (d + 63) / 64; }
+static inline int elem_size(int dt) { return dt == SSV_F32 ? 4 : 2; }
+static inline bool dtype_ok(int dt) { return dt == SSV_F32 || dt == SSV_BF16; }
+
+static int check_shape(int M, int64_t d) {
+    if (M < 1 || M > SSV_MAX_WORKERS || d < 1 || d > SSV_MAX_COORDS) return SSV_ERR_SHAPE;
+    return SSV_OK;
+}
+
+// rows of `es`-byte elements: can every row be read in 16-byte pieces starting at multiples of
+// 16 bytes from its start?
+static inline bool rows_vector_ok(const void* base, int64_t stride, int es, int M) {
+    return aligned(base, 16) && (M == 1 || (stride * es) % 16 == 0);
+}
+
+static int hip_status(hipError_t e) { return e == hipSuccess ? SSV_OK : SSV_ERR_HIP; }
+
+static int step_common(const void* g, int g_dt, float* v, int M, int64_t d, int64_t g_row_stride,
+                       int64_t v_row_stride, float beta, void* x, int x_dt, float lr, float wd, uint64_t* vote_out,
+                       uint64_t* signs_out, int64_t signs_row_stride_words, const uint8_t* worker_flip,
+                       void* stream) {
+    if (g == nullptr) return SSV_ERR_NULL;
+    if (!dtype_ok(g_dt) || (x != nullptr && !dtype_ok(x_dt))) return SSV_ERR_DTYPE;
+    if (int rc = check_shape(M, d)) return rc;
+    const int64_t W = words_for(d);
+    if (g_row_stride < d) return SSV_ERR_SHAPE;
+    if (v != nullptr && v_row_stride < d) return SSV_ERR_SHAPE;
+    if (signs_out != nullptr && signs_row_stride_words < W) return SSV_ERR_SHAPE;
+    if (!(beta >= 0.0f && beta < 1.0f)) return SSV_ERR_PARAM;
+    if (v == nullptr && beta != 0.0f) return SSV_ERR_PARAM;
+    if (x != nullptr && (!std::isfinite(lr) || !std::isfinite(wd))) return SSV_ERR_PARAM;
+    if (!aligned(g, elem_size(g_dt)) || !aligned(v, 4) || !aligned(vote_out, 8) || !aligned(signs_out, 8))
+        return SSV_ERR_ALIGN;
+    if (x != nullptr && !aligned(x, elem_size(x_dt))) return SSV_ERR_ALIGN;
+
+    StepArgs a = {};
+    a.g = g; a.v = v; a.x = x; a.vote_out = vote_out; a.signs_out = signs_out;
+    a.d = d; a.g_stride = g_row_stride; a.v_stride = v_row_stride; a.signs_stride = signs_row_stride_words;
+    a.W = W; a.M = M; a.T = (M + 1) / 2;
+    a.beta = beta; a.omb = 1.0f - beta; a.lr = lr; a.wd = wd;
+    a.has_flip = 0;
+    if (worker_flip != nullptr) {
+        for (int m = 0; m < M; ++m)
+            if (worker_flip[m]) { a.flip.w[m >> 5] |= 1u << (m & 31); a.has_flip = 1; }
+    }
+    bool vec = rows_vector_ok(g, g_row_stride, elem_size(g_dt), M);
+    if (v != nullptr) vec = vec && rows_vector_ok(v, v_row_stride, 4, M);
+    if (x != nullptr) vec = vec && aligned(x, 16);
+    return hip_status(launch_step(a, g_dt, x_dt, vec, static_cast<hipStream_t>(stream)));
+}
+
+static int vote_common(const uint64_t* signs, int M, int64_t d, int64_t stride_words, void* x, int x_dt, float lr,
+                       float wd, uint64_t* vote_out, void* stream) {
+    if (signs == nullptr) return SSV_ERR_NULL;
+    if (x != nullptr && !dtype_ok(x_dt)) return SSV_ERR_DTYPE;
+    if (int rc = check_shape(M, d)) return rc;
+    const int64_t W = words_for(d);
+    if (stride_words < W) return SSV_ERR_SHAPE;
+    if (x != nullptr && (!std::isfinite(lr) || !std::isfinite(wd))) return SSV_ERR_PARAM;
+    if (!aligned(signs, 8) || !aligned(vote_out, 8)) return SSV_ERR_ALIGN;
+    if (x != nullptr && !aligned(x, elem_size(x_dt))) return SSV_ERR_ALIGN;
+    VoteArgs a = {};
+    a.signs = signs; a.vote_out = vote_out; a.x = x;
+    a.d = d; a.W = W; a.stride_words = stride_words; a.M = M; a.lr = lr; a.wd = wd;
+    const bool rows16 = rows_vector_ok(signs, stride_words, 8, M) && aligned(vote_out, 16);
+    const bool xvec = x != nullptr && aligned(x, 16);
+    return hip_status(launch_vote(a, x_dt, rows16, xvec, static_cast<hipStream_t>(stream)));
+}
+
+}  // namespace ssv
+
+using namespace ssv;
+
+extern "C" {
+
+int ssv_sign_pack(const void* x, int dt, int M, int64_t d, int64_t x_row_stride, uint64_t* signs,
+                  int64_t signs_row_stride_words, void* stream) {
+    if (x == nullptr || signs == nullptr) return SSV_ERR_NULL;
+    return step_common(x, dt, nullptr, M, d, x_row_stride, 0, 0.0f, nullptr, SSV_F32, 0.0f, 0.0f, nullptr, signs,
+                       signs_row_stride_words, nullptr, stream);
+}
+
+int ssv_signum_momentum_pack(const void* g, int g_dt, float* v, int M, int64_t d, int64_t g_row_stride,
+                             int64_t v_row_stride, float beta, uint64_t* signs, int64_t signs_row_stride_words,
+                             void* stream) {
+    if (g == nullptr || v == nullptr || signs == nullptr) return SSV_ERR_NULL;
+    return step_common(g, g_dt, v, M, d, g_row_stride, v_row_stride, beta, nullptr, SSV_F32, 0.0f, 0.0f, nullptr,
+                       signs, signs_row_stride_words, nullptr, stream);
+}
+
+int ssv_majority_vote(const uint64_t* signs, int M, int64_t d, int64_t signs_row_stride_words, uint64_t* vote,
+                      void* stream) {
+    if (signs == nullptr || vote == nullptr) return SSV_ERR_NULL;
+    return vote_common(signs, M, d, signs_row_stride_words, nullptr, SSV_F32, 0.0f, 0.0f, vote, stream);
+}
+
+int ssv_apply_sign_update(void* x, int x_dt, int64_t d, const uint64_t* vote, float lr, float weight_decay,
+                          void* stream) {
+    if (x == nullptr || vote == nullptr) return SSV_ERR_NULL;
+    if (!dtype_ok(x_dt)) return SSV_ERR_DTYPE;
+    if (d < 1 || d > SSV_MAX_COORDS) return SSV_ERR_SHAPE;
+    if (!std::isfinite(lr) || !std::isfinite(weight_decay)) return SSV_ERR_PARAM;
+    if (!aligned(x, elem_size(x_dt)) || !aligned(vote, 8)) return SSV_ERR_ALIGN;
+    ApplyArgs a = {x, vote, d, lr, weight_decay};
+    return hip_status(launch_apply(a, x_dt, aligned(x, 16), static_cast<hipStream_t>(stream)));
+}
+
+int ssv_vote_apply(const uint64_t* signs, int M, int64_t d, int64_t signs_row_stride_words, void* x, int x_dt,
+                   float lr, float weight_decay, uint64_t* vote_out, void* stream) {
+    if (signs == nullptr || x == nullptr) return SSV_ERR_NULL;
+    return vote_common(signs, M, d, signs_row_stride_words, x, x_dt, lr, weight_decay, vote_out, stream);
+}
+
+int ssv_signum_step(const void* g, int g_dt, float* v, int M, int64_t d, int64_t g_row_stride, int64_t v_row_stride,
+                    float beta, void* x, int x_dt, float lr, float weight_decay, uint64_t* vote_out,
+                    uint64_t* signs_out, int64_t signs_row_stride_words, const uint8_t* worker_flip, void* stream) {
+    if (g == nullptr || x == nullptr) return SSV_ERR_NULL;
+    return step_common(g, g_dt, v, M, d, g_row_stride, v_row_stride, beta, x, x_dt, lr, weight_decay, vote_out,
+                       signs_out, signs_row_stride_words, worker_flip, stream);
+}
+
+const char* ssv_status_string(int status) {
+    switch (status) {
+        case SSV_OK: return "ok";
+        case SSV_ERR_NULL: return "a required pointer is NULL";
+        case SSV_ERR_SHAPE: return "bad shape: d, M or a row stride out of range";
+        case SSV_ERR_ALIGN: return "a base pointer is not aligned to its element size";
+        case SSV_ERR_DTYPE: return "unknown dtype";
+        case SSV_ERR_PARAM: return "bad parameter: beta outside [0,1), non-finite lr/weight_decay, or momentum without v";
+        case SSV_ERR_HIP: return "the HIP runtime refused the launch";
+        default: return "unknown status";
+    }
+}
+
+int ssv_version(void) { return 1000; }
+
+}  // extern "C"

@@ -1,0 +1,257 @@
+// Server-side kernels on packed sign rows: the majority vote (Algorithm 1, "aggregate sign
+// momenta" + "broadcast majority vote"), optionally fused with the parameter update, and the
+// stand-alone update from a packed vote.
+//
+// The vote never expands to per-coordinate integers.  A lane holds PW 32-bit slices of the row
+// (PW*32 coordinates) and streams the M rows through a carry-save adder network on bit planes:
+// plane p holds bit p of the running count of every coordinate.  Eight rows at a time are reduced
+// with seven full adders (sum = a^b^c, carry = majority(a,b,c): one three-input bit operation
+// each on gfx950) into planes 0..2 and a weight-8 carry that ripples into the upper planes.
+// The counter is preloaded with 2^k - T (T = (M+1)/2 the vote threshold, 2^k > M/2), so the top
+// plane k is directly [count >= T]: no comparator.
+//
+// Work decomposition: a wavefront owns a tile of 64*PW consecutive dwords of every row; lane l
+// loads dwords PW*l .. PW*l+PW-1 of the tile as one 8- or 16-byte piece, so a row access of a
+// wave is one contiguous 512 B / 1 KiB run.  Traffic is (M+1)/8 bytes per coordinate.
+//
+// Fused update: the wave's vote dwords go through a per-wave LDS stage so that the weights can be
+// walked in the order that makes their 16-byte accesses contiguous across lanes.
+#include "device_utils.h"
+
+namespace ssv {
+
+template <int PW>
+__device__ __forceinline__ void load_slices(const uint32_t* __restrict__ p, int nv, uint32_t (&r)[PW]) {
+    // nv = number of this lane's dwords that exist in the row (0, 2 or 4; whole 64-bit words)
+    if constexpr (PW == 2) {
+        if (nv > 0) {
+            u32x2 t = *reinterpret_cast<const u32x2*>(p);
+            r[0] = t.x; r[1] = t.y;
+        } else {
+            r[0] = 0; r[1] = 0;
+        }
+    } else {
+        static_assert(PW == 4, "8- or 16-byte pieces");
+        if (nv == 4) {
+            u32x4 t = *reinterpret_cast<const u32x4*>(p);
+            r[0] = t.x; r[1] = t.y; r[2] = t.z; r[3] = t.w;
+        } else if (nv == 2) {
+            u32x2 t = *reinterpret_cast<const u32x2*>(p);
+            r[0] = t.x; r[1] = t.y; r[2] = 0; r[3] = 0;
+        } else {
+            r[0] = 0; r[1] = 0; r[2] = 0; r[3] = 0;
+        }
+    }
+}
+
+// full adder on bit planes: s <- a ^ b ^ c, returns majority(a, b, c)
+__device__ __forceinline__ uint32_t csa(uint32_t& s, uint32_t a, uint32_t b, uint32_t c) {
+    uint32_t carry = (a & b) | (c & (a ^ b));
+    s = a ^ b ^ c;
+    return carry;
+}
+
+template <int PW, int NPL>
+__device__ __forceinline__ void add_eight_rows(uint32_t (&pl)[NPL][PW], const uint32_t (&r)[8][PW]) {
+#pragma unroll
+    for (int q = 0; q < PW; ++q) {
+        uint32_t ones = pl[0][q], twos = pl[1][q], fours = pl[2][q];
+        uint32_t c1 = csa(ones, ones, r[0][q], r[1][q]);
+        uint32_t c2 = csa(ones, ones, r[2][q], r[3][q]);
+        uint32_t c3 = csa(ones, ones, r[4][q], r[5][q]);
+        uint32_t c4 = csa(ones, ones, r[6][q], r[7][q]);
+        uint32_t d1 = csa(twos, twos, c1, c2);
+        uint32_t d2 = csa(twos, twos, c3, c4);
+        uint32_t e = csa(fours, fours, d1, d2);
+        pl[0][q] = ones; pl[1][q] = twos; pl[2][q] = fours;
+#pragma unroll
+        for (int p = 3; p < NPL - 1; ++p) {
+            uint32_t t = pl[p][q] & e;
+            pl[p][q] ^= e;
+            e = t;
+        }
+        pl[NPL - 1][q] ^= e;   // the preload bound guarantees no carry leaves the top plane
+    }
+}
+
+template <typename XT, int XV>
+__device__ __forceinline__ void apply_piece(XT* __restrict__ xp, int n, uint32_t bits, float lr, float wd) {
+    float xv[XV];
+    load_vals_guarded<XT, XV>(xp, n, xv);
+#pragma unroll
+    for (int c = 0; c < XV; ++c) xv[c] = sign_update(xv[c], ((bits >> c) & 1u) != 0, lr, wd);
+    store_vals_guarded<XT, XV>(xp, n, xv);
+}
+
+// XV = coordinates of x per lane per access (0 = vote only, no update)
+template <int PW, int NPL, typename XT, int XV>
+__global__ __launch_bounds__(kBlock) void vote_kernel(VoteArgs a, int tiles_per_wave, int64_t nblocks, int remap) {
+    __shared__ uint32_t stage[XV > 0 ? kWavesPerBlock : 1][XV > 0 ? kWave * PW : 1];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int64_t lb = logical_block(blockIdx.x, nblocks, remap);
+    if (lb >= nblocks) return;
+    const int64_t ndw = 2 * a.W;
+    const int64_t row_dw = 2 * a.stride_words;
+    const uint32_t* __restrict__ base = reinterpret_cast<const uint32_t*>(a.signs);
+    const int64_t tile0 = lb * (int64_t)(kWavesPerBlock * tiles_per_wave) + wave;
+
+    for (int t = 0; t < tiles_per_wave; ++t) {
+        const int64_t tile = tile0 + (int64_t)t * kWavesPerBlock;
+        if (tile >= a.ntiles) break;
+        const int64_t dw0 = (tile * kWave + lane) * PW;
+        const int64_t left = ndw - dw0;
+        const int nv = left >= PW ? PW : (left > 0 ? (int)left : 0);
+        const uint32_t* p = base + dw0;
+
+        uint32_t pl[NPL][PW];
+#pragma unroll
+        for (int pnum = 0; pnum < NPL; ++pnum)
+#pragma unroll
+            for (int q = 0; q < PW; ++q) pl[pnum][q] = ((a.init >> pnum) & 1u) ? 0xffffffffu : 0u;
+
+        uint32_t cur[8][PW];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) load_slices<PW>(p + (int64_t)i * row_dw, (i < a.M) ? nv : 0, cur[i]);
+        for (int r0 = 0; r0 < a.M; r0 += 8) {
+            uint32_t nxt[8][PW];
+            const int rn = r0 + 8;
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                load_slices<PW>(p + (int64_t)(rn + i) * row_dw, (rn + i < a.M) ? nv : 0, nxt[i]);
+            add_eight_rows<PW, NPL>(pl, cur);
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int q = 0; q < PW; ++q) cur[i][q] = nxt[i][q];
+        }
+
+        uint32_t vt[PW];
+#pragma unroll
+        for (int q = 0; q < PW; ++q) {
+            const int64_t rem = a.d - (dw0 + q) * 32;
+            const uint32_t mask = rem >= 32 ? 0xffffffffu : (rem > 0 ? ((1u << (int)rem) - 1u) : 0u);
+            vt[q] = pl[NPL - 1][q] & mask;
+        }
+        if (a.vote_out != nullptr && nv > 0) {
+            uint32_t* o = reinterpret_cast<uint32_t*>(a.vote_out) + dw0;
+            if constexpr (PW == 4) {
+                if (nv == 4) {
+                    u32x4 w = {vt[0], vt[1], vt[2], vt[3]};
+                    *reinterpret_cast<u32x4*>(o) = w;
+                } else {
+                    u32x2 w = {vt[0], vt[1]};
+                    *reinterpret_cast<u32x2*>(o) = w;
+                }
+            } else {
+                u32x2 w = {vt[0], vt[1]};
+                *reinterpret_cast<u32x2*>(o) = w;
+            }
+        }
+        if constexpr (XV > 0) {
+            // hand the wave's vote dwords over to the lanes that will walk x contiguously
+#pragma unroll
+            for (int q = 0; q < PW; ++q) stage[wave][lane * PW + q] = vt[q];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const int64_t cbase = tile * (int64_t)(kWave * PW * 32);
+            XT* __restrict__ x = static_cast<XT*>(a.x);
+            constexpr int kIter = (PW * 32) / XV;     // accesses per lane to cover the tile
+            constexpr int UA = 4;                      // independent x accesses in flight per lane
+            static_assert(kIter % UA == 0, "tile must split into groups of UA accesses");
+            for (int i0 = 0; i0 < kIter; i0 += UA) {
+                float xv[UA][XV];
+                int n[UA];
+                uint32_t bits[UA];
+#pragma unroll
+                for (int u = 0; u < UA; ++u) {
+                    const int off = (i0 + u) * (kWave * XV) + lane * XV;   // coordinate offset in tile
+                    const int64_t left_c = a.d - (cbase + off);
+                    n[u] = left_c >= XV ? XV : (left_c > 0 ? (int)left_c : 0);
+                    bits[u] = stage[wave][off >> 5] >> (off & 31);
+                    if (n[u] > 0) load_vals_guarded<XT, XV>(x + cbase + off, n[u], xv[u]);
+                }
+#pragma unroll
+                for (int u = 0; u < UA; ++u) {
+                    if (n[u] > 0) {
+                        const int off = (i0 + u) * (kWave * XV) + lane * XV;
+#pragma unroll
+                        for (int c = 0; c < XV; ++c)
+                            xv[u][c] = sign_update(xv[u][c], ((bits[u] >> c) & 1u) != 0, a.lr, a.wd);
+                        store_vals_guarded<XT, XV>(x + cbase + off, n[u], xv[u]);
+                    }
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+}
+
+template <int PW, int NPL, typename XT, int XV>
+static hipError_t launch_vote_one(VoteArgs a, hipStream_t s) {
+    const Tuning& tn = tuning();
+    const int64_t ndw = 2 * a.W;
+    a.ntiles = (ndw + (int64_t)kWave * PW - 1) / ((int64_t)kWave * PW);
+    int tpw = tn.vote_tiles_per_wave > 0 ? tn.vote_tiles_per_wave : 1;
+    int64_t tiles_per_block = (int64_t)kWavesPerBlock * tpw;
+    int64_t nblocks = (a.ntiles + tiles_per_block - 1) / tiles_per_block;
+    int64_t grid = tn.xcd_remap ? 8 * ((nblocks + 7) / 8) : nblocks;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((vote_kernel<PW, NPL, XT, XV>), dim3((unsigned)grid), dim3(kBlock), 0, s, a, tpw, nblocks,
+                       tn.xcd_remap);
+    return hipGetLastError();
+}
+
+template <int PW, int NPL>
+static hipError_t launch_vote_x(const VoteArgs& a, int x_dt, bool x_vector_ok, hipStream_t s) {
+    if (a.x == nullptr) return launch_vote_one<PW, NPL, float, 0>(a, s);
+    if (x_dt == 0)
+        return x_vector_ok ? launch_vote_one<PW, NPL, float, 4>(a, s) : launch_vote_one<PW, NPL, float, 1>(a, s);
+    return x_vector_ok ? launch_vote_one<PW, NPL, bf16, 8>(a, s) : launch_vote_one<PW, NPL, bf16, 1>(a, s);
+}
+
+template <int PW>
+static hipError_t launch_vote_planes(VoteArgs a, int x_dt, bool x_vector_ok, hipStream_t s) {
+    // planes 0..k with 2^k > M/2 and 2^k >= T; template sizes cover M <= 15, 63, 255, 1023
+    const int T = (a.M + 1) / 2;
+    if (a.M <= 15) { a.init = (1u << 3) - T; return launch_vote_x<PW, 4>(a, x_dt, x_vector_ok, s); }
+    if (a.M <= 63) { a.init = (1u << 5) - T; return launch_vote_x<PW, 6>(a, x_dt, x_vector_ok, s); }
+    if (a.M <= 255) { a.init = (1u << 7) - T; return launch_vote_x<PW, 8>(a, x_dt, x_vector_ok, s); }
+    a.init = (1u << 9) - T;
+    return launch_vote_x<PW, 10>(a, x_dt, x_vector_ok, s);
+}
+
+hipError_t launch_vote(const VoteArgs& a, int x_dt, bool rows16, bool x_vector_ok, hipStream_t s) {
+    return rows16 ? launch_vote_planes<4>(a, x_dt, x_vector_ok, s) : launch_vote_planes<2>(a, x_dt, x_vector_ok, s);
+}
+
+// ---- stand-alone update from a packed vote -------------------------------------------------------
+// A lane owns XV consecutive coordinates and reads the byte of the vote that holds their bits.
+template <typename XT, int XV>
+__global__ __launch_bounds__(kBlock) void apply_kernel(ApplyArgs a) {
+    const int64_t j0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * XV;
+    if (j0 >= a.d) return;
+    const int64_t left = a.d - j0;
+    const int n = left >= XV ? XV : (int)left;
+    const uint8_t* __restrict__ vb = reinterpret_cast<const uint8_t*>(a.vote);
+    const uint32_t bits = (uint32_t)vb[j0 >> 3] >> (j0 & 7);
+    apply_piece<XT, XV>(static_cast<XT*>(a.x) + j0, n, bits, a.lr, a.wd);
+}
+
+template <typename XT, int XV>
+static hipError_t launch_apply_one(const ApplyArgs& a, hipStream_t s) {
+    int64_t threads = (a.d + XV - 1) / XV;
+    int64_t grid = (threads + kBlock - 1) / kBlock;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((apply_kernel<XT, XV>), dim3((unsigned)grid), dim3(kBlock), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_apply(const ApplyArgs& a, int x_dt, bool x_vector_ok, hipStream_t s) {
+    if (x_dt == 0) return x_vector_ok ? launch_apply_one<float, 4>(a, s) : launch_apply_one<float, 1>(a, s);
+    return x_vector_ok ? launch_apply_one<bf16, 8>(a, s) : launch_apply_one<bf16, 1>(a, s);
+}
+
+}  // namespace ssv

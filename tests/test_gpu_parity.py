@@ -1,0 +1,344 @@
+"""GPU parity: every entry point of libsignvote, called through its C ABI (via the thin binding),
+against the CPU oracle on the same seeded inputs.  Bars: packed signs and votes bit-exact;
+momentum and weights within 1e-6 relative of the float64 evaluation (and, because both sides fix
+the same fp32 operation order, expected bit-identical to the fp32 oracle -- also asserted)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as ora
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def sv():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU")
+    import paper_1810_05291_amd as sv_
+    sv_.load_library()           # fails loudly when the HIP library is missing
+    return sv_
+
+
+def _log(*a):
+    print(*a, flush=True)
+
+
+def _strided(rows, cols, stride, dtype, fill=None):
+    """[rows, cols] view of a [rows, stride] device buffer."""
+    buf = torch.empty((rows, stride), dtype=dtype, device=DEV)
+    if fill is not None:
+        buf.fill_(fill)
+    return buf, buf[:, :cols]
+
+
+def _np_rows(t):
+    """host copy of a (possibly strided) 2-D device view, contiguous; bf16 -> uint16 bits, int64 -> uint64"""
+    return np.ascontiguousarray(wl.to_numpy(t.contiguous()))
+
+
+RAGGED_D = [1, 3, 63, 64, 65, 255, 256, 257, 511, 1000, 4097, 65536, 100003]
+
+
+# ------------------------------------------------------------------ sign_pack
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("d", RAGGED_D)
+def test_sign_pack_ragged(sv, d, dtype):
+    M = 3
+    for stride in (d, ((d + 31) // 32) * 32, d + 1):
+        _log(f"sign_pack d={d} dtype={dtype} stride={stride}")
+        g = wl.gaussian((M, d), 1.0, seed=d, device=DEV)
+        g[:, ::7] = 0.0
+        buf, view = _strided(M, d, stride, dtype)
+        view.copy_(g)
+        W = sv.words_for(d)
+        sbuf, sview = _strided(M, W, W + 3, torch.int64, fill=-1)
+        sv.sign_pack(view, sview)
+        torch.cuda.synchronize()
+        ref = ora.sign_pack(_np_rows(view))
+        assert np.array_equal(_np_rows(sview), ref)
+        assert (sbuf[:, W:] == -1).all(), "wrote past the row"
+
+
+def test_sign_pack_special_values(sv):
+    x = torch.from_numpy(wl.special_values_f32()).to(DEV)[None, :]
+    got = wl.to_numpy(sv.sign_pack(x))
+    assert np.array_equal(got, ora.sign_pack(wl.special_values_f32()[None, :]))
+    # scalar (unaligned) path sees the same values
+    buf = torch.zeros(64, device=DEV)
+    buf[1:1 + x.shape[1]] = x[0]
+    got2 = wl.to_numpy(sv.sign_pack(buf[1:1 + x.shape[1]][None, :]))
+    assert np.array_equal(got2, got)
+
+
+# ------------------------------------------------------------------ momentum + pack
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("M,d,pad", [(1, 257, 0), (4, 1000, 0), (15, 100003, 0), (15, 100003, 29), (7, 65536, 0),
+                                      (5, 12345, 3)])
+def test_signum_momentum_pack(sv, M, d, pad, dtype):
+    _log(f"momentum_pack M={M} d={d} pad={pad} dtype={dtype}")
+    mu = wl.shared_mean(d, seed=1, device=DEV)
+    _, v = _strided(M, d, d + pad, torch.float32, fill=0.0)
+    v_ref = np.zeros((M, d), np.float32)
+    for step in range(4):
+        g = wl.worker_gradients(mu, M, step, base_seed=100, dtype=dtype, row_stride=d + pad)
+        signs = sv.signum_momentum_pack(g, v, 0.9)
+        torch.cuda.synchronize()
+        g_h = _np_rows(g)
+        g32 = g_h if dtype == torch.float32 else ora.bf16_to_f32(g_h)
+        v64 = ora.momentum_f64(g32, v_ref, 0.9)
+        scale = np.abs(0.1 * g32.astype(np.float64)) + np.abs(0.9 * v_ref.astype(np.float64))
+        signs_ref = ora.signum_momentum_pack(g_h, v_ref, 0.9)
+        v_gpu = _np_rows(v)
+        assert (np.abs(v_gpu - v64) <= 1e-6 * scale + 1e-45).all()
+        assert np.array_equal(v_gpu, v_ref)
+        assert np.array_equal(_np_rows(signs), signs_ref)
+
+
+# ------------------------------------------------------------------ majority vote
+
+VOTE_M = [1, 2, 3, 4, 5, 6, 7, 8, 9, 12, 15, 16, 17, 31, 32, 33, 63, 64, 65, 100, 254, 255, 256, 300, 1023]
+
+
+@pytest.mark.parametrize("M", VOTE_M)
+def test_majority_vote_random_rows(sv, M):
+    for d, extra in ((64 * 700 + 17, 0), (64 * 513, 1), (200, 0), (64 * 129 + 63, 2)):
+        W = sv.words_for(d)
+        _log(f"majority_vote M={M} d={d} stride={W + extra}")
+        buf = wl.random_words((M, W + extra), seed=M * 7 + d, device=DEV)
+        rows = buf[:, :W]
+        vote = sv.majority_vote(rows, d)
+        torch.cuda.synchronize()
+        ref = ora.majority_vote(_np_rows(rows), d)
+        assert np.array_equal(wl.to_numpy(vote), ref)
+
+
+@pytest.mark.parametrize("M", list(range(1, 13)))
+def test_majority_vote_all_patterns(sv, M):
+    # every one of the 2^M sign patterns, one coordinate each
+    d = max(1 << M, 2)
+    idx = np.arange(d, dtype=np.int64)
+    s = np.stack([(((idx >> m) & 1) * 2 - 1).astype(np.int8) for m in range(M)])
+    rows_h = np.stack([ora.pack_signs(s[m]) for m in range(M)])
+    rows = torch.from_numpy(rows_h.view(np.int64)).to(DEV)
+    vote = wl.to_numpy(sv.majority_vote(rows, d))
+    assert np.array_equal(vote, ora.majority_vote(rows_h, d))
+
+
+def test_majority_vote_ignores_and_clears_padding(sv):
+    M, d = 5, 100
+    rows = wl.random_words((M, 2), seed=9, device=DEV)
+    vote = wl.to_numpy(sv.majority_vote(rows, d))
+    rows_h = wl.to_numpy(rows).copy()
+    assert np.array_equal(vote, ora.majority_vote(rows_h, d))
+    assert int(vote[1]) >> 36 == 0
+    rows_h[:, 1] ^= np.uint64(0xFFFFFFF000000000)                      # flip only padding bits
+    vote2 = wl.to_numpy(sv.majority_vote(torch.from_numpy(rows_h.view(np.int64)).to(DEV), d))
+    assert np.array_equal(vote, vote2)
+
+
+# ------------------------------------------------------------------ apply / vote_apply
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("wd", [0.0, 0.01])
+@pytest.mark.parametrize("d", RAGGED_D)
+def test_apply_sign_update(sv, d, wd, dtype):
+    lr = 1e-3 if dtype == torch.float32 else 1e-5
+    for off in (0, 1):                                    # off = 1: base pointer not 16-byte aligned
+        _log(f"apply d={d} wd={wd} dtype={dtype} off={off}")
+        xbuf = wl.gaussian((d + 8,), 0.02, seed=d + 1, device=DEV).to(dtype)
+        x = xbuf[off:off + d]
+        x_h = wl.to_numpy(x.contiguous()).copy()
+        x_before32 = x_h.copy() if dtype == torch.float32 else ora.bf16_to_f32(x_h)
+        vote = wl.random_words((sv.words_for(d),), seed=d, device=DEV)
+        sv.apply_sign_update(x, vote, lr, wd)
+        torch.cuda.synchronize()
+        vote_h = wl.to_numpy(vote)
+        ora.apply_sign_update(x_h, vote_h, lr, wd)
+        got = wl.to_numpy(x.contiguous())
+        assert np.array_equal(got, x_h)
+        x64 = ora.apply_f64(x_before32, ora.unpack_signs(vote_h, d), lr, wd)
+        got32 = got if dtype == torch.float32 else ora.bf16_to_f32(got)
+        # 1e-6 (fp32) or half a bf16 ulp, relative to the magnitude of the operands of the update
+        tol = 1e-6 if dtype == torch.float32 else 2.0 ** -8
+        scale = np.abs(x_before32.astype(np.float64)) * (1 + lr * wd) + lr
+        assert (np.abs(got32 - x64) <= tol * scale).all()
+        # guard elements around the view are untouched
+        ref_buf = wl.gaussian((d + 8,), 0.02, seed=d + 1, device=DEV).to(dtype)
+        assert torch.equal(xbuf[:off], ref_buf[:off]) and torch.equal(xbuf[off + d:], ref_buf[off + d:])
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("M,d,extra,off", [(3, 65536, 0, 0), (15, 100003, 0, 0), (15, 64 * 1001, 1, 0),
+                                            (31, 99999, 0, 1), (255, 20000, 0, 0), (6, 777, 0, 0),
+                                            (16, 64 * 257 + 1, 1, 0), (1, 5, 0, 0)])
+def test_vote_apply(sv, M, d, extra, off, dtype):
+    _log(f"vote_apply M={M} d={d} extra={extra} off={off} dtype={dtype}")
+    W = sv.words_for(d)
+    rows = wl.random_words((M, W + extra), seed=M + d, device=DEV)[:, :W]
+    for wd, want_vote in ((0.0, True), (0.02, False)):
+        xbuf = wl.gaussian((d + 8,), 0.02, seed=5, device=DEV).to(dtype)
+        x = xbuf[off:off + d]
+        x_h = wl.to_numpy(x.contiguous()).copy()
+        vote = torch.full((W,), -1, dtype=torch.int64, device=DEV) if want_vote else None
+        lr = 1e-3 if dtype == torch.float32 else 1e-5
+        sv.vote_apply(rows, d, x, lr, wd, vote_out=vote)
+        torch.cuda.synchronize()
+        vote_ref = ora.vote_apply(_np_rows(rows), d, x_h, lr, wd)
+        assert np.array_equal(wl.to_numpy(x.contiguous()), x_h)
+        if want_vote:
+            assert np.array_equal(wl.to_numpy(vote), vote_ref)
+        ref_buf = wl.gaussian((d + 8,), 0.02, seed=5, device=DEV).to(dtype)
+        assert torch.equal(xbuf[:off], ref_buf[:off]) and torch.equal(xbuf[off + d:], ref_buf[off + d:])
+
+
+# ------------------------------------------------------------------ whole fused step
+
+def _step_case(sv, M, d, g_dtype, x_dtype, beta, wd, steps, pad=0, flip=None, momentum=True, lr=None,
+               x_off=0, noise=1e-2, signal=1e-3):
+    lr = lr if lr is not None else (1e-4 if x_dtype == torch.float32 else 1e-5)
+    mu = wl.shared_mean(d, seed=11, device=DEV, std=signal)
+    xbuf = wl.gaussian((d + 8,), 0.02, seed=12, device=DEV).to(x_dtype)
+    x = xbuf[x_off:x_off + d]
+    x_ref = wl.to_numpy(x.contiguous()).copy()
+    v = v_ref = None
+    if momentum:
+        _, v = _strided(M, d, d + pad, torch.float32, fill=0.0)
+        v_ref = np.zeros((M, d), np.float32)
+    W = sv.words_for(d)
+    near_zero = 0
+    for step in range(steps):
+        g = wl.worker_gradients(mu, M, step, base_seed=500, noise_std=noise, dtype=g_dtype, row_stride=d + pad)
+        vote = torch.full((W,), -1, dtype=torch.int64, device=DEV)
+        signs = torch.full((M, W + 1), -1, dtype=torch.int64, device=DEV)[:, :W]
+        sv.signum_step(g, v, beta, x, lr, wd, vote_out=vote, signs_out=signs, worker_flip=flip)
+        torch.cuda.synchronize()
+        g_h = _np_rows(g)
+        v_prev = None if v_ref is None else v_ref.copy()
+        vote_ref, signs_ref = ora.signum_step(g_h, v_ref, beta, x_ref, lr, wd, want_signs=True, worker_flip=flip)
+        signs_gpu = _np_rows(signs)
+        if momentum:
+            g32 = g_h if g_dtype == torch.float32 else ora.bf16_to_f32(g_h)
+            v64 = ora.momentum_f64(g32, v_prev, beta)
+            v_gpu = _np_rows(v)
+            scale = np.abs((1 - beta) * g32.astype(np.float64)) + np.abs(beta * v_prev.astype(np.float64))
+            assert (np.abs(v_gpu - v64) <= 1e-6 * scale + 1e-45).all(), "momentum outside 1e-6 relative"
+            # sign bits may differ only where |m| < 1e-6 max|m|; count them (expected 0)
+            diff = signs_gpu != signs_ref
+            if diff.any():
+                tiny = np.abs(v64) < 1e-6 * np.abs(v64).max()
+                bad = [ora.unpack_signs(signs_gpu[m], d) != ora.unpack_signs(signs_ref[m], d) for m in range(M)]
+                bad = np.stack(bad)
+                assert not (bad & ~tiny).any(), "sign differs on a decided coordinate"
+                near_zero += int(bad.sum())
+            assert np.array_equal(v_gpu, v_ref), "fp32 momentum not bit-identical to the fp32 oracle"
+        assert np.array_equal(signs_gpu, signs_ref)
+        assert np.array_equal(wl.to_numpy(vote), vote_ref)
+        x_gpu = wl.to_numpy(x.contiguous())
+        assert np.array_equal(x_gpu, x_ref)
+    ref_buf = wl.gaussian((d + 8,), 0.02, seed=12, device=DEV).to(x_dtype)
+    assert torch.equal(xbuf[:x_off], ref_buf[:x_off]) and torch.equal(xbuf[x_off + d:], ref_buf[x_off + d:])
+    return near_zero
+
+
+def test_step_tiny_config_signsgd(sv):
+    # config 'tiny': d = 65,536, M = 3, plain signSGD, lr = 1e-3, one step -- fused and unfused
+    g, x = wl.tiny_config(seed=0, device=DEV)
+    M, d = g.shape
+    x_ref = wl.to_numpy(x).copy()
+    x_f = x.clone()
+    vote = torch.empty((sv.words_for(d),), dtype=torch.int64, device=DEV)
+    sv.signum_step(g, None, 0.0, x_f, 1e-3, vote_out=vote)
+    x_u = x.clone()
+    signs = sv.sign_pack(g)
+    vote_u = sv.majority_vote(signs, d)
+    sv.apply_sign_update(x_u, vote_u, 1e-3)
+    x_v = x.clone()
+    sv.vote_apply(signs, d, x_v, 1e-3)
+    torch.cuda.synchronize()
+    vote_ref, signs_ref = ora.signum_step(wl.to_numpy(g), None, 0.0, x_ref, 1e-3, want_signs=True)
+    assert np.array_equal(wl.to_numpy(signs), signs_ref)
+    assert np.array_equal(wl.to_numpy(vote), vote_ref) and np.array_equal(wl.to_numpy(vote_u), vote_ref)
+    for t in (x_f, x_u, x_v):
+        assert np.array_equal(wl.to_numpy(t), x_ref)
+    x64 = ora.apply_f64(wl.to_numpy(x), ora.unpack_signs(vote_ref, d), 1e-3)
+    assert (np.abs(wl.to_numpy(x_f) - x64) <= 1e-6 * (np.abs(wl.to_numpy(x)) + 1e-3)).all()
+
+
+@pytest.mark.parametrize("M,d,pad,x_off", [(1, 1, 0, 0), (2, 64, 0, 0), (3, 257, 0, 0), (15, 100003, 0, 0),
+                                            (15, 100003, 1, 0), (15, 100000, 0, 1), (31, 70001, 3, 0),
+                                            (16, 4096, 0, 0), (40, 3000, 0, 0)])
+def test_step_signum_fp32(sv, M, d, pad, x_off):
+    _log(f"signum_step fp32 M={M} d={d} pad={pad} x_off={x_off}")
+    nz = _step_case(sv, M, d, torch.float32, torch.float32, 0.9, 0.0, steps=3, pad=pad, x_off=x_off)
+    _log(f"  near-zero sign exceptions: {nz}")
+    assert nz == 0
+
+
+@pytest.mark.parametrize("g_dtype,x_dtype", [(torch.bfloat16, torch.bfloat16), (torch.bfloat16, torch.float32),
+                                              (torch.float32, torch.bfloat16)])
+@pytest.mark.parametrize("M,d,pad", [(31, 100003, 0), (31, 65536 + 8, 0), (5, 999, 5), (3, 8, 0)])
+def test_step_signum_mixed_dtypes(sv, M, d, pad, g_dtype, x_dtype):
+    _log(f"signum_step M={M} d={d} pad={pad} g={g_dtype} x={x_dtype}")
+    assert _step_case(sv, M, d, g_dtype, x_dtype, 0.9, 0.0, steps=2, pad=pad) == 0
+
+
+def test_step_weight_decay_flip_and_no_momentum(sv):
+    flip = [1, 0, 1, 0, 0, 1, 0]
+    assert _step_case(sv, 7, 50001, torch.float32, torch.float32, 0.5, 0.01, steps=2, flip=flip) == 0
+    assert _step_case(sv, 7, 50001, torch.float32, torch.float32, 0.0, 0.0, steps=1, flip=flip, momentum=False) == 0
+    assert _step_case(sv, 6, 3001, torch.bfloat16, torch.bfloat16, 0.0, 0.001, steps=1, momentum=False) == 0
+    # beta = 0 with a momentum buffer: v becomes the gradient
+    assert _step_case(sv, 4, 3001, torch.float32, torch.float32, 0.0, 0.0, steps=2) == 0
+
+
+def test_step_special_values_do_not_spread(sv):
+    # an infinite / NaN gradient from one worker is one vote, nothing more (Section 1 on faulty workers)
+    M, d = 5, 1024
+    g = wl.gaussian((M, d), 1.0, seed=3, device=DEV)
+    g[0, :256] = float("inf")
+    g[0, 256:512] = float("-inf")
+    g[0, 512:768] = float("nan")
+    g[1, ::3] = 0.0
+    g[2, ::5] = -0.0
+    x = wl.gaussian((d,), 0.02, seed=4, device=DEV)
+    v = torch.zeros((M, d), device=DEV)
+    x_ref, v_ref = wl.to_numpy(x).copy(), np.zeros((M, d), np.float32)
+    vote = torch.empty((sv.words_for(d),), dtype=torch.int64, device=DEV)
+    signs = torch.empty((M, sv.words_for(d)), dtype=torch.int64, device=DEV)
+    for _ in range(2):
+        sv.signum_step(g, v, 0.9, x, 1e-3, vote_out=vote, signs_out=signs)
+        torch.cuda.synchronize()
+        vote_ref, signs_ref = ora.signum_step(wl.to_numpy(g), v_ref, 0.9, x_ref, 1e-3, want_signs=True)
+        assert np.array_equal(wl.to_numpy(signs), signs_ref)
+        assert np.array_equal(wl.to_numpy(vote), vote_ref)
+        assert np.array_equal(wl.to_numpy(x), x_ref)
+        v_gpu = wl.to_numpy(v)
+        nan = np.isnan(v_ref)                      # NaN payloads are not compared, NaN-ness is
+        assert np.array_equal(np.isnan(v_gpu), nan) and np.array_equal(v_gpu[~nan], v_ref[~nan])
+    assert np.isfinite(wl.to_numpy(x)).all()
+
+
+def test_argument_errors_leave_buffers_untouched(sv):
+    lib = sv.load_library()
+    d, M = 1000, 3
+    g = wl.gaussian((M, d), 1.0, seed=1, device=DEV)
+    x = wl.gaussian((d,), 0.02, seed=2, device=DEV)
+    x0 = x.clone()
+    signs = torch.full((M, sv.words_for(d)), 7, dtype=torch.int64, device=DEV)
+    with pytest.raises(sv.SignvoteError) as e:
+        sv.signum_step(g, None, 0.9, x, 1e-3)             # momentum asked without v
+    assert e.value.status == -5
+    assert lib.ssv_sign_pack(g.data_ptr(), 0, 0, d, d, signs.data_ptr(), signs.stride(0), None) == -2
+    assert lib.ssv_sign_pack(g.data_ptr(), 0, M, d, d - 1, signs.data_ptr(), signs.stride(0), None) == -2
+    assert lib.ssv_sign_pack(g.data_ptr(), 5, M, d, d, signs.data_ptr(), signs.stride(0), None) == -4
+    assert lib.ssv_sign_pack(g.data_ptr() + 2, 0, M, d, d, signs.data_ptr(), signs.stride(0), None) == -3
+    assert lib.ssv_majority_vote(signs.data_ptr(), 1024, d, signs.stride(0), signs.data_ptr(), None) == -2
+    assert lib.ssv_apply_sign_update(x.data_ptr(), 0, d, signs.data_ptr(), float("nan"), 0.0, None) == -5
+    torch.cuda.synchronize()
+    assert torch.equal(x, x0) and (signs == 7).all()
