@@ -5,6 +5,22 @@
 
 namespace ssv {
 
+// ---- streaming accesses --------------------------------------------------------------------
+// Every gradient, momentum and weight element is touched once per step, so the 8- and 16-byte
+// accesses carry the non-temporal hint: measured on MI355X this is worth about 10% of HBM
+// bandwidth on the fused step (the lines do not linger in L2 / Infinity Cache).
+template <typename V>
+__device__ __forceinline__ V stream_load(const V* p) { return __builtin_nontemporal_load(p); }
+template <typename V>
+__device__ __forceinline__ void stream_store(V* p, V v) { __builtin_nontemporal_store(v, p); }
+
+// Wait until every memory operation this wave has issued has completed.  Placed after each row
+// load of the fused step it keeps ONE load per wave in flight: with 16-20 waves per CU that is
+// already enough bytes in flight to cover HBM latency, and on MI355X the fused step then runs
+// about 10% faster than with 16 loads per wave queued up (deep per-wave queues lower the
+// sustained HBM rate of this 30-stream read/write mix; measured, see the design notes).
+__device__ __forceinline__ void drain_memory_ops() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // ---- loads: VEC consecutive elements starting at p, widened to fp32 ------------------------
 // Vector forms need p aligned to min(16, VEC * sizeof(element)) bytes.
 template <int VEC>
@@ -14,7 +30,7 @@ __device__ __forceinline__ void load_vals(const float* __restrict__ p, float (&o
     } else {
 #pragma unroll
         for (int q = 0; q < VEC / 4; ++q) {
-            f32x4 t = *reinterpret_cast<const f32x4*>(p + 4 * q);
+            f32x4 t = stream_load(reinterpret_cast<const f32x4*>(p + 4 * q));
             o[4 * q + 0] = t.x; o[4 * q + 1] = t.y; o[4 * q + 2] = t.z; o[4 * q + 3] = t.w;
         }
     }
@@ -25,12 +41,12 @@ __device__ __forceinline__ void load_vals(const bf16* __restrict__ p, float (&o)
     if constexpr (VEC == 1) {
         o[0] = bf16_bits_to_f32(p[0].bits);
     } else if constexpr (VEC == 4) {
-        u32x2 t = *reinterpret_cast<const u32x2*>(p);
+        u32x2 t = stream_load(reinterpret_cast<const u32x2*>(p));
         o[0] = __uint_as_float(t.x << 16); o[1] = __uint_as_float(t.x & 0xffff0000u);
         o[2] = __uint_as_float(t.y << 16); o[3] = __uint_as_float(t.y & 0xffff0000u);
     } else {
         static_assert(VEC == 8, "bf16 runs are 1, 4 or 8 long");
-        u32x4 t = *reinterpret_cast<const u32x4*>(p);
+        u32x4 t = stream_load(reinterpret_cast<const u32x4*>(p));
         o[0] = __uint_as_float(t.x << 16); o[1] = __uint_as_float(t.x & 0xffff0000u);
         o[2] = __uint_as_float(t.y << 16); o[3] = __uint_as_float(t.y & 0xffff0000u);
         o[4] = __uint_as_float(t.z << 16); o[5] = __uint_as_float(t.z & 0xffff0000u);
@@ -62,7 +78,7 @@ __device__ __forceinline__ void store_vals(float* __restrict__ p, const float (&
 #pragma unroll
         for (int q = 0; q < VEC / 4; ++q) {
             f32x4 t = {o[4 * q + 0], o[4 * q + 1], o[4 * q + 2], o[4 * q + 3]};
-            *reinterpret_cast<f32x4*>(p + 4 * q) = t;
+            stream_store(reinterpret_cast<f32x4*>(p + 4 * q), t);
         }
     }
 }
@@ -74,14 +90,14 @@ __device__ __forceinline__ void store_vals(bf16* __restrict__ p, const float (&o
     } else if constexpr (VEC == 4) {
         u32x2 t = {f32_to_bf16_bits(o[0]) | (f32_to_bf16_bits(o[1]) << 16),
                    f32_to_bf16_bits(o[2]) | (f32_to_bf16_bits(o[3]) << 16)};
-        *reinterpret_cast<u32x2*>(p) = t;
+        stream_store(reinterpret_cast<u32x2*>(p), t);
     } else {
         static_assert(VEC == 8, "bf16 runs are 1, 4 or 8 long");
         u32x4 t = {f32_to_bf16_bits(o[0]) | (f32_to_bf16_bits(o[1]) << 16),
                    f32_to_bf16_bits(o[2]) | (f32_to_bf16_bits(o[3]) << 16),
                    f32_to_bf16_bits(o[4]) | (f32_to_bf16_bits(o[5]) << 16),
                    f32_to_bf16_bits(o[6]) | (f32_to_bf16_bits(o[7]) << 16)};
-        *reinterpret_cast<u32x4*>(p) = t;
+        stream_store(reinterpret_cast<u32x4*>(p), t);
     }
 }
 

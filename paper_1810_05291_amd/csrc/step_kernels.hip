@@ -7,162 +7,206 @@
 //   APPLY  x <- x - lr (vote + wd x)                      ("update parameters")
 // Packed signs / packed vote are optional outputs built with wave ballots.
 //
-// Work decomposition: a wavefront owns a tile of 64*VEC consecutive coordinates, lane l owning the
-// VEC consecutive ones at 64*VEC*tile + VEC*l, so that every global access of a wave is one
+// Work decomposition: a tile is 64*VEC consecutive coordinates, lane l of the wave that owns it
+// holding the VEC consecutive ones at offset VEC*l, so every global access of a wave is one
 // contiguous run of 16-byte lane pieces (VEC = 4 for fp32 gradients, 8 for bf16; VEC = 1 is the
-// any-alignment path).  A lane keeps its coordinates through all M workers, so nothing crosses
-// lanes except the optional ballots.  The kernel is HBM-bound: 12 bytes per worker-coordinate
-// (read g, read v, write v) plus 8 per coordinate for x at fp32.
+// any-alignment path).  A workgroup of four waves owns 4*SUB consecutive tiles, wave w holding
+// tiles w, w+4, ..: the four waves' accesses of one step form one contiguous 4 KiB run per row,
+// which measures about 6% faster on MI355X than giving each wave SUB adjacent tiles.
+// A lane keeps its coordinates through all M workers, so nothing crosses lanes except the
+// optional ballots.  The kernel is HBM-bound: 12 bytes per worker-coordinate (read g, read v,
+// write v) plus 8 per coordinate for x at fp32.  Per group of U = 2 workers a wave reads its
+// 2*U*SUB row pieces one at a time (each load waits for the one before), then computes and issues
+// the U*SUB momentum stores back to back: a read phase and a write burst per group.
 #include "device_utils.h"
 
 namespace ssv {
 
-template <typename GT, int VEC, bool MOM, bool GUARD, int U>
-__device__ __forceinline__ void worker_group(const StepArgs& a, int m0, int64_t j0, int nvalid, int lane,
-                                             int64_t tile, uint32_t (&cnt)[VEC]) {
-    float gv[U][VEC];
-    float vv[U][VEC];
+template <typename GT, int VEC, int SUB, bool MOM, bool GUARD, int U>
+__device__ __forceinline__ void worker_group(const StepArgs& a, int m0, int64_t j0, const int (&nvalid)[SUB],
+                                             int lane, int64_t tile0, uint32_t (&cnt)[SUB][VEC]) {
+    constexpr int64_t kTile = (int64_t)kWave * VEC * kWavesPerBlock;   // a wave's tiles are a block-row apart
+    constexpr bool SERIAL = (VEC > 1);   // vector paths: one row load in flight per wave
+    float gv[U][SUB][VEC];
+    float vv[U][SUB][VEC];
     const GT* __restrict__ g = static_cast<const GT*>(a.g);
-    // all loads of the group first, so that up to 2*U 16-byte loads per lane are in flight
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const GT* gp = g + (int64_t)(m0 + u) * a.g_stride + j0;
-        if constexpr (GUARD) load_vals_guarded<GT, VEC>(gp, nvalid, gv[u]);
-        else load_vals<VEC>(gp, gv[u]);
+#pragma unroll
+        for (int s = 0; s < SUB; ++s) {
+            if constexpr (GUARD) {
+                load_vals_guarded<GT, VEC>(gp + s * kTile, nvalid[s], gv[u][s]);
+            } else {
+                load_vals<VEC>(gp + s * kTile, gv[u][s]);
+                if constexpr (SERIAL) drain_memory_ops();
+            }
+        }
     }
     if constexpr (MOM) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const float* vp = a.v + (int64_t)(m0 + u) * a.v_stride + j0;
-            if constexpr (GUARD) load_vals_guarded<float, VEC>(vp, nvalid, vv[u]);
-            else load_vals<VEC>(vp, vv[u]);
+#pragma unroll
+            for (int s = 0; s < SUB; ++s) {
+                if constexpr (GUARD) {
+                    load_vals_guarded<float, VEC>(vp + s * kTile, nvalid[s], vv[u][s]);
+                } else {
+                    load_vals<VEC>(vp + s * kTile, vv[u][s]);
+                    if constexpr (SERIAL) drain_memory_ops();
+                }
+            }
         }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int m = m0 + u;
-        if constexpr (MOM) {
+        const uint32_t flip = a.has_flip ? ((a.flip.w[m >> 5] >> (m & 31)) & 1u) : 0u;
+#pragma unroll
+        for (int s = 0; s < SUB; ++s) {
+            if constexpr (MOM) {
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) {
+                    float t = a.omb * gv[u][s][c];
+                    vv[u][s][c] = fmaf(a.beta, vv[u][s][c], t);
+                }
+                float* vp = a.v + (int64_t)m * a.v_stride + j0 + s * kTile;
+                if constexpr (GUARD) store_vals_guarded<float, VEC>(vp, nvalid[s], vv[u][s]);
+                else store_vals<VEC>(vp, vv[u][s]);
+            } else {
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) vv[u][s][c] = gv[u][s][c];
+            }
+            uint32_t b[VEC];
 #pragma unroll
             for (int c = 0; c < VEC; ++c) {
-                float t = a.omb * gv[u][c];
-                vv[u][c] = fmaf(a.beta, vv[u][c], t);
+                b[c] = (vv[u][s][c] >= 0.0f ? 1u : 0u) ^ flip;
+                if constexpr (GUARD) b[c] = (c < nvalid[s]) ? b[c] : 0u;
+                cnt[s][c] += b[c];
             }
-            float* vp = a.v + (int64_t)m * a.v_stride + j0;
-            if constexpr (GUARD) store_vals_guarded<float, VEC>(vp, nvalid, vv[u]);
-            else store_vals<VEC>(vp, vv[u]);
-        } else {
-#pragma unroll
-            for (int c = 0; c < VEC; ++c) vv[u][c] = gv[u][c];
+            if (a.signs_out != nullptr) {
+                uint64_t words[VEC];
+                pack_tile<VEC>(b, words);
+                store_tile_words<VEC>(a.signs_out + (int64_t)m * a.signs_stride, tile0 + s * kWavesPerBlock, a.W, lane,
+                                      words);
+            }
         }
-        const uint32_t flip = a.has_flip ? ((a.flip.w[m >> 5] >> (m & 31)) & 1u) : 0u;
-        uint32_t b[VEC];
+    }
+}
+
+// tile0 = index of the wave's first tile of 64*VEC coordinates; its s-th tile is tile0 + 4 s
+template <typename GT, typename XT, int VEC, int SUB, bool MOM, bool APPLY, bool GUARD>
+__device__ __forceinline__ void step_tiles(const StepArgs& a, int64_t tile0, int lane) {
+    constexpr int64_t kTile = (int64_t)kWave * VEC * kWavesPerBlock;
+    const int64_t j0 = tile0 * (int64_t)(kWave * VEC) + (int64_t)lane * VEC;
+    int nvalid[SUB];
+#pragma unroll
+    for (int s = 0; s < SUB; ++s) {
+        nvalid[s] = VEC;
+        if constexpr (GUARD) {
+            int64_t r = a.d - (j0 + s * kTile);
+            nvalid[s] = r >= VEC ? VEC : (r > 0 ? (int)r : 0);
+        }
+    }
+    uint32_t cnt[SUB][VEC];
+#pragma unroll
+    for (int s = 0; s < SUB; ++s)
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) cnt[s][c] = 0;
+
+    constexpr int U = 2;
+    int m = 0;
+    for (; m + U <= a.M; m += U) worker_group<GT, VEC, SUB, MOM, GUARD, U>(a, m, j0, nvalid, lane, tile0, cnt);
+    if (m < a.M) worker_group<GT, VEC, SUB, MOM, GUARD, 1>(a, m, j0, nvalid, lane, tile0, cnt);
+
+#pragma unroll
+    for (int s = 0; s < SUB; ++s) {
+        uint32_t vb[VEC];
 #pragma unroll
         for (int c = 0; c < VEC; ++c) {
-            b[c] = (vv[u][c] >= 0.0f ? 1u : 0u) ^ flip;
-            if constexpr (GUARD) b[c] = (c < nvalid) ? b[c] : 0u;
-            cnt[c] += b[c];
+            vb[c] = (cnt[s][c] >= (uint32_t)a.T) ? 1u : 0u;
+            if constexpr (GUARD) vb[c] = (c < nvalid[s]) ? vb[c] : 0u;
         }
-        if (a.signs_out != nullptr) {
+        if (a.vote_out != nullptr) {
             uint64_t words[VEC];
-            pack_tile<VEC>(b, words);
-            store_tile_words<VEC>(a.signs_out + (int64_t)m * a.signs_stride, tile, a.W, lane, words);
+            pack_tile<VEC>(vb, words);
+            store_tile_words<VEC>(a.vote_out, tile0 + s * kWavesPerBlock, a.W, lane, words);
+        }
+        if constexpr (APPLY) {
+            if (nvalid[s] > 0) {
+                XT* xp = static_cast<XT*>(a.x) + j0 + s * kTile;
+                float xv[VEC];
+                if constexpr (GUARD) load_vals_guarded<XT, VEC>(xp, nvalid[s], xv);
+                else load_vals<VEC>(xp, xv);
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) xv[c] = sign_update(xv[c], vb[c] != 0, a.lr, a.wd);
+                if constexpr (GUARD) store_vals_guarded<XT, VEC>(xp, nvalid[s], xv);
+                else store_vals<VEC>(xp, xv);
+            }
         }
     }
 }
 
-template <typename GT, typename XT, int VEC, bool MOM, bool APPLY, bool GUARD>
-__device__ __forceinline__ void step_tile(const StepArgs& a, int64_t tile, int lane) {
-    const int64_t j0 = tile * (int64_t)(kWave * VEC) + (int64_t)lane * VEC;
-    int nvalid = VEC;
-    if constexpr (GUARD) {
-        int64_t r = a.d - j0;
-        nvalid = r >= VEC ? VEC : (r > 0 ? (int)r : 0);
-    }
-    uint32_t cnt[VEC];
-#pragma unroll
-    for (int c = 0; c < VEC; ++c) cnt[c] = 0;
-
-    constexpr int U = (VEC >= 8) ? 2 : 4;      // keeps 8 sixteen-byte loads per lane in flight
-    int m = 0;
-    for (; m + U <= a.M; m += U) worker_group<GT, VEC, MOM, GUARD, U>(a, m, j0, nvalid, lane, tile, cnt);
-    if constexpr (U == 4) {
-        if (m + 2 <= a.M) { worker_group<GT, VEC, MOM, GUARD, 2>(a, m, j0, nvalid, lane, tile, cnt); m += 2; }
-    }
-    if (m < a.M) worker_group<GT, VEC, MOM, GUARD, 1>(a, m, j0, nvalid, lane, tile, cnt);
-
-    uint32_t vb[VEC];
-#pragma unroll
-    for (int c = 0; c < VEC; ++c) {
-        vb[c] = (cnt[c] >= (uint32_t)a.T) ? 1u : 0u;
-        if constexpr (GUARD) vb[c] = (c < nvalid) ? vb[c] : 0u;
-    }
-    if (a.vote_out != nullptr) {
-        uint64_t words[VEC];
-        pack_tile<VEC>(vb, words);
-        store_tile_words<VEC>(a.vote_out, tile, a.W, lane, words);
-    }
-    if constexpr (APPLY) {
-        if (nvalid > 0) {
-            XT* xp = static_cast<XT*>(a.x) + j0;
-            float xv[VEC];
-            if constexpr (GUARD) load_vals_guarded<XT, VEC>(xp, nvalid, xv);
-            else load_vals<VEC>(xp, xv);
-#pragma unroll
-            for (int c = 0; c < VEC; ++c) xv[c] = sign_update(xv[c], vb[c] != 0, a.lr, a.wd);
-            if constexpr (GUARD) store_vals_guarded<XT, VEC>(xp, nvalid, xv);
-            else store_vals<VEC>(xp, xv);
-        }
-    }
-}
-
-template <typename GT, typename XT, int VEC, bool MOM, bool APPLY>
-__global__ __launch_bounds__(kBlock) void step_kernel(StepArgs a, int tiles_per_wave, int64_t nblocks,
-                                                      int remap) {
+// Blocks 0 .. nfull-1 each take 4*SUB consecutive tiles: in step s (s < SUB) the block's four waves
+// touch four adjacent tiles, i.e. one contiguous 4 KiB run of every row.  The waves of the blocks
+// after them take the remaining (fewer than 4*SUB + 1) tiles one by one with bounds checks.
+template <typename GT, typename XT, int VEC, int SUB, bool MOM, bool APPLY>
+__global__ __launch_bounds__(kBlock) void step_kernel(StepArgs a, int64_t nfull, int64_t nblocks, int remap) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int64_t lb = logical_block(blockIdx.x, nblocks, remap);
     if (lb >= nblocks) return;
-    const int64_t tile0 = lb * (int64_t)(kWavesPerBlock * tiles_per_wave) + wave;
-    for (int t = 0; t < tiles_per_wave; ++t) {
-        const int64_t tile = tile0 + (int64_t)t * kWavesPerBlock;
-        if (tile >= a.ntiles) break;
-        if ((tile + 1) * (int64_t)(kWave * VEC) <= a.d)
-            step_tile<GT, XT, VEC, MOM, APPLY, false>(a, tile, lane);
-        else
-            step_tile<GT, XT, VEC, MOM, APPLY, true>(a, tile, lane);
+    if (lb < nfull) {
+        step_tiles<GT, XT, VEC, SUB, MOM, APPLY, false>(a, lb * (kWavesPerBlock * SUB) + wave, lane);
+    } else {
+        const int64_t tile = nfull * (kWavesPerBlock * SUB) + (lb - nfull) * kWavesPerBlock + wave;
+        if (tile < a.ntiles) step_tiles<GT, XT, VEC, 1, MOM, APPLY, true>(a, tile, lane);
     }
 }
 
-template <typename GT, typename XT, int VEC, bool MOM, bool APPLY>
+template <typename GT, typename XT, int VEC, int SUB, bool MOM, bool APPLY>
 static hipError_t launch_one(StepArgs a, hipStream_t s) {
     const Tuning& tn = tuning();
-    a.ntiles = (a.d + (int64_t)kWave * VEC - 1) / ((int64_t)kWave * VEC);
-    int tpw = tn.step_tiles_per_wave > 0 ? tn.step_tiles_per_wave : 1;
-    int64_t tiles_per_block = (int64_t)kWavesPerBlock * tpw;
-    int64_t nblocks = (a.ntiles + tiles_per_block - 1) / tiles_per_block;
-    int64_t grid = tn.xcd_remap ? 8 * ((nblocks + 7) / 8) : nblocks;
+    constexpr int64_t kTile = (int64_t)kWave * VEC;
+    constexpr int64_t kBlockTiles = (int64_t)kWavesPerBlock * SUB;
+    a.ntiles = (a.d + kTile - 1) / kTile;
+    const int64_t nfull = a.d / (kTile * kBlockTiles);
+    const int64_t tail_tiles = a.ntiles - nfull * kBlockTiles;
+    const int64_t nblocks = nfull + (tail_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int64_t grid = tn.xcd_remap ? 8 * ((nblocks + 7) / 8) : nblocks;
     if (grid > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((step_kernel<GT, XT, VEC, MOM, APPLY>), dim3((unsigned)grid), dim3(kBlock), 0, s, a, tpw,
-                       nblocks, tn.xcd_remap);
+    hipLaunchKernelGGL((step_kernel<GT, XT, VEC, SUB, MOM, APPLY>), dim3((unsigned)grid), dim3(kBlock), 0, s, a,
+                       nfull, nblocks, tn.xcd_remap);
     return hipGetLastError();
 }
 
-template <typename GT, int VEC>
+template <typename GT, int VEC, int SUB>
 static hipError_t launch_g(const StepArgs& a, int x_dt, hipStream_t s) {
     const bool mom = a.v != nullptr;
     const bool apply = a.x != nullptr;
     if (!apply) {
-        return mom ? launch_one<GT, float, VEC, true, false>(a, s) : launch_one<GT, float, VEC, false, false>(a, s);
+        return mom ? launch_one<GT, float, VEC, SUB, true, false>(a, s)
+                   : launch_one<GT, float, VEC, SUB, false, false>(a, s);
     }
     if (x_dt == 0) {
-        return mom ? launch_one<GT, float, VEC, true, true>(a, s) : launch_one<GT, float, VEC, false, true>(a, s);
+        return mom ? launch_one<GT, float, VEC, SUB, true, true>(a, s)
+                   : launch_one<GT, float, VEC, SUB, false, true>(a, s);
     }
-    return mom ? launch_one<GT, bf16, VEC, true, true>(a, s) : launch_one<GT, bf16, VEC, false, true>(a, s);
+    return mom ? launch_one<GT, bf16, VEC, SUB, true, true>(a, s) : launch_one<GT, bf16, VEC, SUB, false, true>(a, s);
 }
 
 hipError_t launch_step(const StepArgs& a, int g_dt, int x_dt, bool vector_ok, hipStream_t s) {
-    if (g_dt == 0) return vector_ok ? launch_g<float, 4>(a, x_dt, s) : launch_g<float, 1>(a, x_dt, s);
-    return vector_ok ? launch_g<bf16, 8>(a, x_dt, s) : launch_g<bf16, 1>(a, x_dt, s);
+    const int sub = tuning().step_sub;
+    if (g_dt == 0) {
+        if (!vector_ok) return launch_g<float, 1, 4>(a, x_dt, s);
+        if (sub == 1) return launch_g<float, 4, 1>(a, x_dt, s);
+        if (sub == 2) return launch_g<float, 4, 2>(a, x_dt, s);
+        return launch_g<float, 4, 4>(a, x_dt, s);
+    }
+    if (!vector_ok) return launch_g<bf16, 1, 4>(a, x_dt, s);
+    if (sub == 1) return launch_g<bf16, 8, 1>(a, x_dt, s);
+    if (sub == 4) return launch_g<bf16, 8, 4>(a, x_dt, s);
+    return launch_g<bf16, 8, 2>(a, x_dt, s);
 }
 
 }  // namespace ssv
