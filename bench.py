@@ -27,7 +27,7 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workers", type=int, default=15)
     ap.add_argument("--d", type=int, default=25_557_032)
-    ap.add_argument("--row-align", type=int, default=1,
+    ap.add_argument("--row-align", type=int, default=32,
                     help="round row strides up to a multiple of this many elements")
     ap.add_argument("--grad-sets", type=int, default=8, help="distinct pre-generated gradient sets that are cycled")
     ap.add_argument("--no-cpu-baseline", action="store_true")

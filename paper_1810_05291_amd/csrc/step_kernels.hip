@@ -22,7 +22,7 @@
 
 namespace ssv {
 
-template <typename GT, int VEC, int SUB, bool MOM, bool GUARD, int U>
+template <typename GT, int VEC, int SUB, bool MOM, bool OUT, bool GUARD, int U>
 __device__ __forceinline__ void worker_group(const StepArgs& a, int m0, int64_t j0, const int (&nvalid)[SUB],
                                              int lane, int64_t tile0, uint32_t (&cnt)[SUB][VEC]) {
     constexpr int64_t kTile = (int64_t)kWave * VEC * kWavesPerBlock;   // a wave's tiles are a block-row apart
@@ -61,7 +61,8 @@ __device__ __forceinline__ void worker_group(const StepArgs& a, int m0, int64_t 
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int m = m0 + u;
-        const uint32_t flip = a.has_flip ? ((a.flip.w[m >> 5] >> (m & 31)) & 1u) : 0u;
+        uint32_t flip = 0u;
+        if constexpr (OUT) flip = a.has_flip ? ((a.flip.w[m >> 5] >> (m & 31)) & 1u) : 0u;
 #pragma unroll
         for (int s = 0; s < SUB; ++s) {
             if constexpr (MOM) {
@@ -84,7 +85,7 @@ __device__ __forceinline__ void worker_group(const StepArgs& a, int m0, int64_t 
                 if constexpr (GUARD) b[c] = (c < nvalid[s]) ? b[c] : 0u;
                 cnt[s][c] += b[c];
             }
-            if (a.signs_out != nullptr) {
+            if (OUT && a.signs_out != nullptr) {
                 uint64_t words[VEC];
                 pack_tile<VEC>(b, words);
                 store_tile_words<VEC>(a.signs_out + (int64_t)m * a.signs_stride, tile0 + s * kWavesPerBlock, a.W, lane,
@@ -95,7 +96,7 @@ __device__ __forceinline__ void worker_group(const StepArgs& a, int m0, int64_t 
 }
 
 // tile0 = index of the wave's first tile of 64*VEC coordinates; its s-th tile is tile0 + 4 s
-template <typename GT, typename XT, int VEC, int SUB, bool MOM, bool APPLY, bool GUARD>
+template <typename GT, typename XT, int VEC, int SUB, bool MOM, bool APPLY, bool OUT, bool GUARD>
 __device__ __forceinline__ void step_tiles(const StepArgs& a, int64_t tile0, int lane) {
     constexpr int64_t kTile = (int64_t)kWave * VEC * kWavesPerBlock;
     const int64_t j0 = tile0 * (int64_t)(kWave * VEC) + (int64_t)lane * VEC;
@@ -116,8 +117,8 @@ __device__ __forceinline__ void step_tiles(const StepArgs& a, int64_t tile0, int
 
     constexpr int U = 2;
     int m = 0;
-    for (; m + U <= a.M; m += U) worker_group<GT, VEC, SUB, MOM, GUARD, U>(a, m, j0, nvalid, lane, tile0, cnt);
-    if (m < a.M) worker_group<GT, VEC, SUB, MOM, GUARD, 1>(a, m, j0, nvalid, lane, tile0, cnt);
+    for (; m + U <= a.M; m += U) worker_group<GT, VEC, SUB, MOM, OUT, GUARD, U>(a, m, j0, nvalid, lane, tile0, cnt);
+    if (m < a.M) worker_group<GT, VEC, SUB, MOM, OUT, GUARD, 1>(a, m, j0, nvalid, lane, tile0, cnt);
 
 #pragma unroll
     for (int s = 0; s < SUB; ++s) {
@@ -127,7 +128,7 @@ __device__ __forceinline__ void step_tiles(const StepArgs& a, int64_t tile0, int
             vb[c] = (cnt[s][c] >= (uint32_t)a.T) ? 1u : 0u;
             if constexpr (GUARD) vb[c] = (c < nvalid[s]) ? vb[c] : 0u;
         }
-        if (a.vote_out != nullptr) {
+        if (OUT && a.vote_out != nullptr) {
             uint64_t words[VEC];
             pack_tile<VEC>(vb, words);
             store_tile_words<VEC>(a.vote_out, tile0 + s * kWavesPerBlock, a.W, lane, words);
@@ -150,22 +151,23 @@ __device__ __forceinline__ void step_tiles(const StepArgs& a, int64_t tile0, int
 // Blocks 0 .. nfull-1 each take 4*SUB consecutive tiles: in step s (s < SUB) the block's four waves
 // touch four adjacent tiles, i.e. one contiguous 4 KiB run of every row.  The waves of the blocks
 // after them take the remaining (fewer than 4*SUB + 1) tiles one by one with bounds checks.
-template <typename GT, typename XT, int VEC, int SUB, bool MOM, bool APPLY>
+// OUT = false is the lean form without optional outputs (packed signs, packed vote, flips).
+template <typename GT, typename XT, int VEC, int SUB, bool MOM, bool APPLY, bool OUT>
 __global__ __launch_bounds__(kBlock) void step_kernel(StepArgs a, int64_t nfull, int64_t nblocks, int remap) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int64_t lb = logical_block(blockIdx.x, nblocks, remap);
     if (lb >= nblocks) return;
     if (lb < nfull) {
-        step_tiles<GT, XT, VEC, SUB, MOM, APPLY, false>(a, lb * (kWavesPerBlock * SUB) + wave, lane);
+        step_tiles<GT, XT, VEC, SUB, MOM, APPLY, OUT, false>(a, lb * (kWavesPerBlock * SUB) + wave, lane);
     } else {
         const int64_t tile = nfull * (kWavesPerBlock * SUB) + (lb - nfull) * kWavesPerBlock + wave;
-        if (tile < a.ntiles) step_tiles<GT, XT, VEC, 1, MOM, APPLY, true>(a, tile, lane);
+        if (tile < a.ntiles) step_tiles<GT, XT, VEC, 1, MOM, APPLY, OUT, true>(a, tile, lane);
     }
 }
 
-template <typename GT, typename XT, int VEC, int SUB, bool MOM, bool APPLY>
-static hipError_t launch_one(StepArgs a, hipStream_t s) {
+template <typename GT, typename XT, int VEC, int SUB, bool MOM, bool APPLY, bool OUT>
+static hipError_t launch_out(StepArgs a, hipStream_t s) {
     const Tuning& tn = tuning();
     constexpr int64_t kTile = (int64_t)kWave * VEC;
     constexpr int64_t kBlockTiles = (int64_t)kWavesPerBlock * SUB;
@@ -175,9 +177,17 @@ static hipError_t launch_one(StepArgs a, hipStream_t s) {
     const int64_t nblocks = nfull + (tail_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
     const int64_t grid = tn.xcd_remap ? 8 * ((nblocks + 7) / 8) : nblocks;
     if (grid > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((step_kernel<GT, XT, VEC, SUB, MOM, APPLY>), dim3((unsigned)grid), dim3(kBlock), 0, s, a,
+    hipLaunchKernelGGL((step_kernel<GT, XT, VEC, SUB, MOM, APPLY, OUT>), dim3((unsigned)grid), dim3(kBlock), 0, s, a,
                        nfull, nblocks, tn.xcd_remap);
     return hipGetLastError();
+}
+
+template <typename GT, typename XT, int VEC, int SUB, bool MOM, bool APPLY>
+static hipError_t launch_one(const StepArgs& a, hipStream_t s) {
+    const bool out = a.signs_out != nullptr || a.vote_out != nullptr || a.has_flip;
+    if constexpr (!APPLY) return launch_out<GT, XT, VEC, SUB, MOM, APPLY, true>(a, s);   // pack-only forms
+    else return out ? launch_out<GT, XT, VEC, SUB, MOM, APPLY, true>(a, s)
+                    : launch_out<GT, XT, VEC, SUB, MOM, APPLY, false>(a, s);
 }
 
 template <typename GT, int VEC, int SUB>
