@@ -31,6 +31,10 @@ def parse_args():
                     help="round row strides up to a multiple of this many elements")
     ap.add_argument("--grad-sets", type=int, default=8, help="distinct pre-generated gradient sets that are cycled")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="instead of the benchmark, run a plain 1 GiB device-to-device copy three times "
+                         "(known traffic: 1 GiB read + 1 GiB written per copy) to scale rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--cpu-sample", type=int, default=1 << 22, help="coordinates in the oracle's timed sample")
     return ap.parse_args()
 
@@ -64,6 +68,16 @@ def main():
         hip_build.build()
     sv.load_library()
     dev = "cuda:0"
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": "3 copies", "bytes_read_each": src.numel() * 4,
+                          "bytes_written_each": src.numel() * 4}))
+        return
     M, d, K, Wm = args.workers, args.d, args.steps, args.warmup
     beta, lr = 0.9, 1e-4
     stride = ((d + args.row_align - 1) // args.row_align) * args.row_align
