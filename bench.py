@@ -31,6 +31,9 @@ def parse_args():
                     help="round row strides up to a multiple of this many elements")
     ap.add_argument("--grad-sets", type=int, default=8, help="distinct pre-generated gradient sets that are cycled")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--other-kernels", action="store_true",
+                    help="also time the packed vote (d = 2^30, M = 255), the fused vote+apply (resnet50 size) and "
+                         "the bf16 fused step (M = 31, chunk of 2^26) and add them to the JSON line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="instead of the benchmark, run a plain 1 GiB device-to-device copy three times "
                          "(known traffic: 1 GiB read + 1 GiB written per copy) to scale rocprofv3's "
@@ -50,6 +53,58 @@ def read_traffic(name):
     except OSError:
         pass
     return None
+
+
+def time_launches(torch, fn, iters, warmup=2):
+    """Average milliseconds per call of fn() over `iters` back-to-back launches (events on the current stream)."""
+    for i in range(warmup):
+        fn(i)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(iters):
+        fn(warmup + i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def other_kernels(torch, sv, wl, dev):
+    """Secondary measurements: the kernels that are not the headline, at their own workloads."""
+    out = {}
+    # packed majority vote, d = 2^30, M = 255 (uniform random bits: the kernel is data-oblivious)
+    M, d = 255, 1 << 30
+    W = sv.words_for(d)
+    rows = wl.random_words((M, W), seed=5, device=dev)
+    vote = torch.empty((W,), dtype=torch.int64, device=dev)
+    ms = time_launches(torch, lambda i: sv.majority_vote(rows, d, vote), 10)
+    b = (M + 1) / 8 * d
+    out["majority_vote_d2^30_M255"] = {"ms": ms, "GB/s": b / ms / 1e6, "frac": b / ms / 1e6 / HBM_PEAK_GBS,
+                                        "coords_per_s": d / ms * 1e3, "algorithmic_bytes": b}
+    del rows, vote
+    # fused vote + apply at the resnet50 size, 8 rotating buffer sets (2 GB, beyond the 256 MB Infinity Cache)
+    M, d = 15, 25_557_032
+    W = sv.words_for(d)
+    sets = [(wl.random_words((M, W), seed=10 + k, device=dev), wl.gaussian((d,), 0.02, seed=20 + k, device=dev))
+            for k in range(8)]
+    ms = time_launches(torch, lambda i: sv.vote_apply(sets[i % 8][0], d, sets[i % 8][1], 1e-4), 80, warmup=8)
+    b = (M / 8 + 8) * d
+    out["vote_apply_resnet50_M15"] = {"ms": ms, "GB/s": b / ms / 1e6, "frac": b / ms / 1e6 / HBM_PEAK_GBS,
+                                      "algorithmic_bytes": b, "note": "8 rotating buffer sets"}
+    del sets
+    # bf16 fused step, M = 31, one chunk of 2^26 coordinates out of a 2^28-coordinate momentum (row stride 2^28)
+    M, chunk, nch = 31, 1 << 26, 4
+    dd = chunk * nch
+    v = torch.zeros((M, dd), device=dev)
+    x = wl.gaussian((dd,), 0.02, seed=3, device=dev).to(torch.bfloat16)
+    mu = wl.shared_mean(chunk, seed=4, device=dev)
+    g = wl.worker_gradients(mu, M, 0, base_seed=7, dtype=torch.bfloat16)
+    ms = time_launches(torch, lambda i: sv.signum_step(g, v[:, (i % nch) * chunk:(i % nch + 1) * chunk], 0.9,
+                                                       x[(i % nch) * chunk:(i % nch + 1) * chunk], 1e-5), 12, warmup=4)
+    b = (10 * M + 4) * chunk
+    out["signum_step_bf16_M31_chunk2^26"] = {"ms": ms, "GB/s": b / ms / 1e6, "frac": b / ms / 1e6 / HBM_PEAK_GBS,
+                                             "algorithmic_bytes": b}
+    return out
 
 
 def main():
@@ -159,6 +214,10 @@ def main():
         "cpu_baseline": cpu,
         "parity": parity,
     }
+    if args.other_kernels:
+        del grads, v, x, mu
+        torch.cuda.empty_cache()
+        out["other_kernels"] = other_kernels(torch, sv, wl, dev)
     print(json.dumps(out), flush=True)
     if parity is not None and parity.startswith("MISMATCH"):
         sys.exit(1)

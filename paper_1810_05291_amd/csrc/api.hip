@@ -14,8 +14,7 @@ static int env_int(const char* name) {
 }
 
 const Tuning& tuning() {
-    static const Tuning t = {env_int("SSV_TUNE_STEP_SUB"), env_int("SSV_TUNE_VOTE_TILES_PER_WAVE"),
-                             env_int("SSV_TUNE_XCD_REMAP")};
+    static const Tuning t = {env_int("SSV_TUNE_STEP_SUB"), env_int("SSV_TUNE_XCD_REMAP")};
     return t;
 }
 

@@ -71,7 +71,6 @@ hipError_t launch_apply(const ApplyArgs& a, int x_dt, bool x_vector_ok, hipStrea
 // Launch-shape knobs, read once from the environment (SSV_TUNE_*); 0 / unset = built-in default.
 struct Tuning {
     int step_sub;              // tiles a wave of the step kernel holds at once (1, 2 or 4)
-    int vote_tiles_per_wave;
     int xcd_remap;             // 1 = give each XCD a contiguous range of tiles
 };
 const Tuning& tuning();

@@ -10,22 +10,36 @@
 // The counter is preloaded with 2^k - T (T = (M+1)/2 the vote threshold, 2^k > M/2), so the top
 // plane k is directly [count >= T]: no comparator.
 //
-// Work decomposition: a wavefront owns a tile of 64*PW consecutive dwords of every row; lane l
-// loads dwords PW*l .. PW*l+PW-1 of the tile as one 8- or 16-byte piece, so a row access of a
+// Vote only (vote_kernel): a wavefront owns a tile of 64*PW consecutive dwords of every row; lane
+// l loads dwords PW*l .. PW*l+PW-1 of the tile as one 8- or 16-byte piece, so a row access of a
 // wave is one contiguous 512 B / 1 KiB run.  Traffic is (M+1)/8 bytes per coordinate.
 //
-// Fused update: the wave's vote dwords go through a per-wave LDS stage so that the weights can be
-// walked in the order that makes their 16-byte accesses contiguous across lanes.
+// Fused vote + update (vote_apply_kernel): a workgroup owns 256 consecutive dwords of every row
+// (8192 coordinates), one dword per thread; the 256 vote dwords go through LDS, and the
+// workgroup then walks its 8192 weights in contiguous 4 KiB steps.  Traffic is M/8 + 8 bytes
+// per coordinate at fp32 and is dominated by the weights.
 #include "device_utils.h"
 
+#ifndef SSV_APPLY_UA
+#define SSV_APPLY_UA 4
+#endif
+#ifndef SSV_APPLY_SERIAL
+#define SSV_APPLY_SERIAL 0
+#endif
+
 namespace ssv {
+
+// Packed rows are read once: streaming loads.  Unlike the fused gradient step, this pure-read
+// stream runs fastest with all eight row loads of a batch in flight (84% of HBM peak at M = 255).
+template <typename V>
+__device__ __forceinline__ V row_load(const V* p) { return stream_load(p); }
 
 template <int PW>
 __device__ __forceinline__ void load_slices(const uint32_t* __restrict__ p, int nv, uint32_t (&r)[PW]) {
     // nv = number of this lane's dwords that exist in the row (0, 2 or 4; whole 64-bit words)
     if constexpr (PW == 2) {
         if (nv > 0) {
-            u32x2 t = *reinterpret_cast<const u32x2*>(p);
+            u32x2 t = row_load(reinterpret_cast<const u32x2*>(p));
             r[0] = t.x; r[1] = t.y;
         } else {
             r[0] = 0; r[1] = 0;
@@ -33,10 +47,10 @@ __device__ __forceinline__ void load_slices(const uint32_t* __restrict__ p, int 
     } else {
         static_assert(PW == 4, "8- or 16-byte pieces");
         if (nv == 4) {
-            u32x4 t = *reinterpret_cast<const u32x4*>(p);
+            u32x4 t = row_load(reinterpret_cast<const u32x4*>(p));
             r[0] = t.x; r[1] = t.y; r[2] = t.z; r[3] = t.w;
         } else if (nv == 2) {
-            u32x2 t = *reinterpret_cast<const u32x2*>(p);
+            u32x2 t = row_load(reinterpret_cast<const u32x2*>(p));
             r[0] = t.x; r[1] = t.y; r[2] = 0; r[3] = 0;
         } else {
             r[0] = 0; r[1] = 0; r[2] = 0; r[3] = 0;
@@ -83,49 +97,46 @@ __device__ __forceinline__ void apply_piece(XT* __restrict__ xp, int n, uint32_t
     store_vals_guarded<XT, XV>(xp, n, xv);
 }
 
-// XV = coordinates of x per lane per access (0 = vote only, no update)
-template <int PW, int NPL, typename XT, int XV>
-__global__ __launch_bounds__(kBlock) void vote_kernel(VoteArgs a, int tiles_per_wave, int64_t nblocks, int remap) {
-    __shared__ uint32_t stage[XV > 0 ? kWavesPerBlock : 1][XV > 0 ? kWave * PW : 1];
+template <int PW, int NPL>
+__global__ __launch_bounds__(kBlock) void vote_kernel(VoteArgs a, int64_t nblocks, int remap) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int64_t lb = logical_block(blockIdx.x, nblocks, remap);
     if (lb >= nblocks) return;
+    const int64_t tile = lb * kWavesPerBlock + wave;
+    if (tile >= a.ntiles) return;
     const int64_t ndw = 2 * a.W;
     const int64_t row_dw = 2 * a.stride_words;
-    const uint32_t* __restrict__ base = reinterpret_cast<const uint32_t*>(a.signs);
-    const int64_t tile0 = lb * (int64_t)(kWavesPerBlock * tiles_per_wave) + wave;
+    const int64_t dw0 = (tile * kWave + lane) * PW;
+    const int64_t left = ndw - dw0;
+    const int nv = left >= PW ? PW : (left > 0 ? (int)left : 0);
+    const uint32_t* __restrict__ p = reinterpret_cast<const uint32_t*>(a.signs) + dw0;
 
-    for (int t = 0; t < tiles_per_wave; ++t) {
-        const int64_t tile = tile0 + (int64_t)t * kWavesPerBlock;
-        if (tile >= a.ntiles) break;
-        const int64_t dw0 = (tile * kWave + lane) * PW;
-        const int64_t left = ndw - dw0;
-        const int nv = left >= PW ? PW : (left > 0 ? (int)left : 0);
-        const uint32_t* p = base + dw0;
+    uint32_t pl[NPL][PW];
+#pragma unroll
+    for (int pnum = 0; pnum < NPL; ++pnum)
+#pragma unroll
+        for (int q = 0; q < PW; ++q) pl[pnum][q] = ((a.init >> pnum) & 1u) ? 0xffffffffu : 0u;
 
-        uint32_t pl[NPL][PW];
+    // Batches of eight rows.  The loads of the next batch are written after the adder network of
+    // the current one; the compiler is free to issue them early (loads only, nothing aliases).
+    uint32_t cur[8][PW];
 #pragma unroll
-        for (int pnum = 0; pnum < NPL; ++pnum)
+    for (int i = 0; i < 8; ++i) load_slices<PW>(p + (int64_t)i * row_dw, (i < a.M) ? nv : 0, cur[i]);
+    for (int r0 = 0; r0 < a.M; r0 += 8) {
+        uint32_t nxt[8][PW];
+        const int rn = r0 + 8;
+        add_eight_rows<PW, NPL>(pl, cur);
 #pragma unroll
-            for (int q = 0; q < PW; ++q) pl[pnum][q] = ((a.init >> pnum) & 1u) ? 0xffffffffu : 0u;
+        for (int i = 0; i < 8; ++i)
+            load_slices<PW>(p + (int64_t)(rn + i) * row_dw, (rn + i < a.M) ? nv : 0, nxt[i]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int q = 0; q < PW; ++q) cur[i][q] = nxt[i][q];
+    }
 
-        uint32_t cur[8][PW];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) load_slices<PW>(p + (int64_t)i * row_dw, (i < a.M) ? nv : 0, cur[i]);
-        for (int r0 = 0; r0 < a.M; r0 += 8) {
-            uint32_t nxt[8][PW];
-            const int rn = r0 + 8;
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                load_slices<PW>(p + (int64_t)(rn + i) * row_dw, (rn + i < a.M) ? nv : 0, nxt[i]);
-            add_eight_rows<PW, NPL>(pl, cur);
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-#pragma unroll
-                for (int q = 0; q < PW; ++q) cur[i][q] = nxt[i][q];
-        }
-
+    if (nv > 0) {
         uint32_t vt[PW];
 #pragma unroll
         for (int q = 0; q < PW; ++q) {
@@ -133,98 +144,122 @@ __global__ __launch_bounds__(kBlock) void vote_kernel(VoteArgs a, int tiles_per_
             const uint32_t mask = rem >= 32 ? 0xffffffffu : (rem > 0 ? ((1u << (int)rem) - 1u) : 0u);
             vt[q] = pl[NPL - 1][q] & mask;
         }
-        if (a.vote_out != nullptr && nv > 0) {
-            uint32_t* o = reinterpret_cast<uint32_t*>(a.vote_out) + dw0;
-            if constexpr (PW == 4) {
-                if (nv == 4) {
-                    u32x4 w = {vt[0], vt[1], vt[2], vt[3]};
-                    *reinterpret_cast<u32x4*>(o) = w;
-                } else {
-                    u32x2 w = {vt[0], vt[1]};
-                    *reinterpret_cast<u32x2*>(o) = w;
-                }
+        uint32_t* o = reinterpret_cast<uint32_t*>(a.vote_out) + dw0;
+        if constexpr (PW == 4) {
+            if (nv == 4) {
+                u32x4 w = {vt[0], vt[1], vt[2], vt[3]};
+                *reinterpret_cast<u32x4*>(o) = w;
             } else {
                 u32x2 w = {vt[0], vt[1]};
                 *reinterpret_cast<u32x2*>(o) = w;
             }
-        }
-        if constexpr (XV > 0) {
-            // hand the wave's vote dwords over to the lanes that will walk x contiguously
-#pragma unroll
-            for (int q = 0; q < PW; ++q) stage[wave][lane * PW + q] = vt[q];
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            const int64_t cbase = tile * (int64_t)(kWave * PW * 32);
-            XT* __restrict__ x = static_cast<XT*>(a.x);
-            constexpr int kIter = (PW * 32) / XV;     // accesses per lane to cover the tile
-            constexpr int UA = 4;                      // independent x accesses in flight per lane
-            static_assert(kIter % UA == 0, "tile must split into groups of UA accesses");
-            for (int i0 = 0; i0 < kIter; i0 += UA) {
-                float xv[UA][XV];
-                int n[UA];
-                uint32_t bits[UA];
-#pragma unroll
-                for (int u = 0; u < UA; ++u) {
-                    const int off = (i0 + u) * (kWave * XV) + lane * XV;   // coordinate offset in tile
-                    const int64_t left_c = a.d - (cbase + off);
-                    n[u] = left_c >= XV ? XV : (left_c > 0 ? (int)left_c : 0);
-                    bits[u] = stage[wave][off >> 5] >> (off & 31);
-                    if (n[u] > 0) load_vals_guarded<XT, XV>(x + cbase + off, n[u], xv[u]);
-                }
-#pragma unroll
-                for (int u = 0; u < UA; ++u) {
-                    if (n[u] > 0) {
-                        const int off = (i0 + u) * (kWave * XV) + lane * XV;
-#pragma unroll
-                        for (int c = 0; c < XV; ++c)
-                            xv[u][c] = sign_update(xv[u][c], ((bits[u] >> c) & 1u) != 0, a.lr, a.wd);
-                        store_vals_guarded<XT, XV>(x + cbase + off, n[u], xv[u]);
-                    }
-                }
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
+        } else {
+            u32x2 w = {vt[0], vt[1]};
+            *reinterpret_cast<u32x2*>(o) = w;
         }
     }
 }
 
-template <int PW, int NPL, typename XT, int XV>
-static hipError_t launch_vote_one(VoteArgs a, hipStream_t s) {
-    const Tuning& tn = tuning();
+// Fused vote + update.  XV = weights per thread per access (4 fp32 / 8 bf16; 1 = any alignment).
+template <int NPL, typename XT, int XV>
+__global__ __launch_bounds__(kBlock) void vote_apply_kernel(VoteArgs a) {
+    __shared__ uint32_t stage[kBlock];
+    constexpr int kTileCoords = kBlock * 32;
+    const int t = threadIdx.x;
+    const int64_t tile = blockIdx.x;
     const int64_t ndw = 2 * a.W;
-    a.ntiles = (ndw + (int64_t)kWave * PW - 1) / ((int64_t)kWave * PW);
-    int tpw = tn.vote_tiles_per_wave > 0 ? tn.vote_tiles_per_wave : 1;
-    int64_t tiles_per_block = (int64_t)kWavesPerBlock * tpw;
-    int64_t nblocks = (a.ntiles + tiles_per_block - 1) / tiles_per_block;
-    int64_t grid = tn.xcd_remap ? 8 * ((nblocks + 7) / 8) : nblocks;
-    if (grid > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((vote_kernel<PW, NPL, XT, XV>), dim3((unsigned)grid), dim3(kBlock), 0, s, a, tpw, nblocks,
-                       tn.xcd_remap);
-    return hipGetLastError();
+    const int64_t row_dw = 2 * a.stride_words;
+    const int64_t dw = tile * kBlock + t;
+    const bool have = dw < ndw;
+    const uint32_t* __restrict__ p = reinterpret_cast<const uint32_t*>(a.signs) + dw;
+
+    uint32_t pl[NPL][1];
+#pragma unroll
+    for (int pnum = 0; pnum < NPL; ++pnum) pl[pnum][0] = ((a.init >> pnum) & 1u) ? 0xffffffffu : 0u;
+    for (int r0 = 0; r0 < a.M; r0 += 8) {
+        uint32_t cur[8][1];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            cur[i][0] = (have && r0 + i < a.M) ? row_load(p + (int64_t)(r0 + i) * row_dw) : 0u;
+        add_eight_rows<1, NPL>(pl, cur);
+    }
+    const int64_t rem = a.d - dw * 32;
+    const uint32_t mask = rem >= 32 ? 0xffffffffu : (rem > 0 ? ((1u << (int)rem) - 1u) : 0u);
+    const uint32_t vt = pl[NPL - 1][0] & mask;
+    if (a.vote_out != nullptr && have) reinterpret_cast<uint32_t*>(a.vote_out)[dw] = vt;
+    stage[t] = vt;
+    __syncthreads();     // every thread of the workgroup reaches this: no early exits above
+
+    XT* __restrict__ x = static_cast<XT*>(a.x);
+    const int64_t cbase = tile * (int64_t)kTileCoords;
+    constexpr int kIter = 32 / XV;                 // accesses per thread to cover the tile
+    constexpr int UA = (kIter % SSV_APPLY_UA == 0) ? SSV_APPLY_UA : 1;
+    for (int i0 = 0; i0 < kIter; i0 += UA) {
+        float xv[UA][XV];
+        int n[UA];
+        uint32_t bits[UA];
+#pragma unroll
+        for (int u = 0; u < UA; ++u) {
+            const int off = (i0 + u) * (kBlock * XV) + t * XV;      // coordinate offset inside the tile
+            const int64_t left_c = a.d - (cbase + off);
+            n[u] = left_c >= XV ? XV : (left_c > 0 ? (int)left_c : 0);
+            bits[u] = stage[off >> 5] >> (off & 31);
+            if (n[u] > 0) load_vals_guarded<XT, XV>(x + cbase + off, n[u], xv[u]);
+#if SSV_APPLY_SERIAL
+            drain_memory_ops();
+#endif
+        }
+#pragma unroll
+        for (int u = 0; u < UA; ++u) {
+            if (n[u] > 0) {
+                const int off = (i0 + u) * (kBlock * XV) + t * XV;
+#pragma unroll
+                for (int c = 0; c < XV; ++c)
+                    xv[u][c] = sign_update(xv[u][c], ((bits[u] >> c) & 1u) != 0, a.lr, a.wd);
+                store_vals_guarded<XT, XV>(x + cbase + off, n[u], xv[u]);
+            }
+        }
+    }
 }
 
 template <int PW, int NPL>
-static hipError_t launch_vote_x(const VoteArgs& a, int x_dt, bool x_vector_ok, hipStream_t s) {
-    if (a.x == nullptr) return launch_vote_one<PW, NPL, float, 0>(a, s);
+static hipError_t launch_vote_only(VoteArgs a, hipStream_t s) {
+    const Tuning& tn = tuning();
+    const int64_t ndw = 2 * a.W;
+    a.ntiles = (ndw + (int64_t)kWave * PW - 1) / ((int64_t)kWave * PW);
+    const int64_t nblocks = (a.ntiles + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int64_t grid = tn.xcd_remap ? 8 * ((nblocks + 7) / 8) : nblocks;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((vote_kernel<PW, NPL>), dim3((unsigned)grid), dim3(kBlock), 0, s, a, nblocks, tn.xcd_remap);
+    return hipGetLastError();
+}
+
+template <int NPL, typename XT, int XV>
+static hipError_t launch_vote_apply_one(VoteArgs a, hipStream_t s) {
+    const int64_t ndw = 2 * a.W;
+    a.ntiles = (ndw + kBlock - 1) / kBlock;
+    if (a.ntiles > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((vote_apply_kernel<NPL, XT, XV>), dim3((unsigned)a.ntiles), dim3(kBlock), 0, s, a);
+    return hipGetLastError();
+}
+
+template <int NPL>
+static hipError_t launch_vote_npl(const VoteArgs& a, int x_dt, bool rows16, bool x_vector_ok, hipStream_t s) {
+    if (a.x == nullptr) return rows16 ? launch_vote_only<4, NPL>(a, s) : launch_vote_only<2, NPL>(a, s);
     if (x_dt == 0)
-        return x_vector_ok ? launch_vote_one<PW, NPL, float, 4>(a, s) : launch_vote_one<PW, NPL, float, 1>(a, s);
-    return x_vector_ok ? launch_vote_one<PW, NPL, bf16, 8>(a, s) : launch_vote_one<PW, NPL, bf16, 1>(a, s);
+        return x_vector_ok ? launch_vote_apply_one<NPL, float, 4>(a, s) : launch_vote_apply_one<NPL, float, 1>(a, s);
+    return x_vector_ok ? launch_vote_apply_one<NPL, bf16, 8>(a, s) : launch_vote_apply_one<NPL, bf16, 1>(a, s);
 }
 
-template <int PW>
-static hipError_t launch_vote_planes(VoteArgs a, int x_dt, bool x_vector_ok, hipStream_t s) {
+hipError_t launch_vote(const VoteArgs& a_in, int x_dt, bool rows16, bool x_vector_ok, hipStream_t s) {
     // planes 0..k with 2^k > M/2 and 2^k >= T; template sizes cover M <= 15, 63, 255, 1023
+    VoteArgs a = a_in;
     const int T = (a.M + 1) / 2;
-    if (a.M <= 15) { a.init = (1u << 3) - T; return launch_vote_x<PW, 4>(a, x_dt, x_vector_ok, s); }
-    if (a.M <= 63) { a.init = (1u << 5) - T; return launch_vote_x<PW, 6>(a, x_dt, x_vector_ok, s); }
-    if (a.M <= 255) { a.init = (1u << 7) - T; return launch_vote_x<PW, 8>(a, x_dt, x_vector_ok, s); }
+    if (a.M <= 15) { a.init = (1u << 3) - T; return launch_vote_npl<4>(a, x_dt, rows16, x_vector_ok, s); }
+    if (a.M <= 63) { a.init = (1u << 5) - T; return launch_vote_npl<6>(a, x_dt, rows16, x_vector_ok, s); }
+    if (a.M <= 255) { a.init = (1u << 7) - T; return launch_vote_npl<8>(a, x_dt, rows16, x_vector_ok, s); }
     a.init = (1u << 9) - T;
-    return launch_vote_x<PW, 10>(a, x_dt, x_vector_ok, s);
-}
-
-hipError_t launch_vote(const VoteArgs& a, int x_dt, bool rows16, bool x_vector_ok, hipStream_t s) {
-    return rows16 ? launch_vote_planes<4>(a, x_dt, x_vector_ok, s) : launch_vote_planes<2>(a, x_dt, x_vector_ok, s);
+    return launch_vote_npl<10>(a, x_dt, rows16, x_vector_ok, s);
 }
 
 // ---- stand-alone update from a packed vote -------------------------------------------------------
