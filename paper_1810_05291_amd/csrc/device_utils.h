@@ -124,57 +124,36 @@ __device__ __forceinline__ float sign_update(float x, bool plus, float lr, float
 }
 
 // ---- packing -------------------------------------------------------------------------------
-// spread<VEC>(x): move bit i of x (i < 64 / VEC) to bit VEC * i.
+// A wavefront owns a tile of 64 * VEC consecutive coordinates, lane l owning VEC * l .. VEC * l +
+// VEC - 1 with bit b[c] for its c-th one.  The tile's words (bit i of word k <-> coordinate
+// 64 k + i of the tile) are written to row[tile * VEC + k], for the words that lie inside the
+// row of W words.
+//
+// VEC = 1: the wave ballot IS the word.
+// VEC = 4: each lane shifts its 4-bit group to its place inside the dword that 8 neighbouring
+// lanes share, and three DPP steps (lane ^ 1, lane ^ 2, mirror inside the half row) OR the eight
+// groups together; the first lane of every eight then stores its dword.  A handful of vector
+// instructions per tile; an interleave of four ballot masks on the scalar unit costs ~200.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_or(uint32_t v) {
+    return v | (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+
 template <int VEC>
-__device__ __forceinline__ uint64_t spread_bits(uint64_t x) {
+__device__ __forceinline__ void pack_store_tile(uint64_t* __restrict__ row, int64_t tile, int64_t W, int lane,
+                                                const uint32_t (&b)[VEC]) {
     if constexpr (VEC == 1) {
-        return x;
-    } else if constexpr (VEC == 4) {
-        x = (x | (x << 24)) & 0x000000FF000000FFull;
-        x = (x | (x << 12)) & 0x000F000F000F000Full;
-        x = (x | (x << 6)) & 0x0303030303030303ull;
-        x = (x | (x << 3)) & 0x1111111111111111ull;
-        return x;
+        const uint64_t word = __ballot(b[0] != 0);
+        if (lane == 0 && tile < W) row[tile] = word;
     } else {
-        static_assert(VEC == 8, "1, 4 or 8 coordinates per lane");
-        x = (x | (x << 28)) & 0x0000000F0000000Full;
-        x = (x | (x << 14)) & 0x0003000300030003ull;
-        x = (x | (x << 7)) & 0x0101010101010101ull;
-        return x;
+        static_assert(VEC == 4, "1 or 4 coordinates per lane");
+        uint32_t v = (b[0] | (b[1] << 1) | (b[2] << 2) | (b[3] << 3)) << (4 * (lane & 7));
+        v = dpp_or<0xB1>(v);     // quad_perm [1,0,3,2]
+        v = dpp_or<0x4E>(v);     // quad_perm [2,3,0,1]
+        v = dpp_or<0x141>(v);    // row_half_mirror
+        const int64_t dw = tile * 8 + (lane >> 3);          // dword index inside the packed row
+        if ((lane & 7) == 0 && (dw >> 1) < W) reinterpret_cast<uint32_t*>(row)[dw] = v;
     }
-}
-
-// A wavefront owns 64 * VEC consecutive coordinates, lane l owning VEC * l .. VEC * l + VEC - 1
-// with bit b[c] for its c-th one.  Returns in words[k] the k-th 64-bit word of that run (bit i of
-// word k <-> coordinate 64 k + i).  One wave ballot per c; the interleave is scalar work.
-template <int VEC>
-__device__ __forceinline__ void pack_tile(const uint32_t (&b)[VEC], uint64_t (&words)[VEC]) {
-    uint64_t ballots[VEC];
-#pragma unroll
-    for (int c = 0; c < VEC; ++c) ballots[c] = __ballot(b[c] != 0);
-    constexpr int kLanesPerWord = kWave / VEC;
-    constexpr uint64_t kChunkMask = (VEC == 1) ? ~0ull : ((1ull << (kLanesPerWord % 64)) - 1ull);
-#pragma unroll
-    for (int k = 0; k < VEC; ++k) {
-        uint64_t w = 0;
-#pragma unroll
-        for (int c = 0; c < VEC; ++c) {
-            uint64_t chunk = (VEC == 1) ? ballots[c] : ((ballots[c] >> (k * kLanesPerWord)) & kChunkMask);
-            w |= spread_bits<VEC>(chunk) << c;
-        }
-        words[k] = w;
-    }
-}
-
-// Lane k (< VEC) stores word k of the tile if it lies inside the row of W words.
-template <int VEC>
-__device__ __forceinline__ void store_tile_words(uint64_t* __restrict__ row, int64_t tile, int64_t W,
-                                                 int lane, const uint64_t (&words)[VEC]) {
-    uint64_t mine = words[0];
-#pragma unroll
-    for (int k = 1; k < VEC; ++k) mine = (lane == k) ? words[k] : mine;
-    int64_t w = tile * VEC + lane;
-    if (lane < VEC && w < W) row[w] = mine;
 }
 
 // Physical block id -> logical block id.  Workgroups are handed to the 8 XCDs round-robin; with

@@ -5,7 +5,8 @@
 //   count  per-coordinate count of set bits over the M workers, kept in registers
 //          ("aggregate sign momenta"); vote bit = [count >= (M+1)/2]
 //   APPLY  x <- x - lr (vote + wd x)                      ("update parameters")
-// Packed signs / packed vote are optional outputs built with wave ballots.
+// Packed signs / packed vote are optional outputs (ballot at one coordinate per lane, a DPP
+// merge of 4-bit lane groups at four).
 //
 // Work decomposition: a tile is 64*VEC consecutive coordinates, lane l of the wave that owns it
 // holding the VEC consecutive ones at offset VEC*l, so every global access of a wave is one
@@ -20,13 +21,19 @@
 // the U*SUB momentum stores back to back: a read phase and a write burst per group.
 #include "device_utils.h"
 
+#ifndef SSV_SERIAL_READONLY
+#define SSV_SERIAL_READONLY 0
+#endif
+
 namespace ssv {
 
 template <typename GT, int VEC, int SUB, bool MOM, bool OUT, bool GUARD, int U>
 __device__ __forceinline__ void worker_group(const StepArgs& a, int m0, int64_t j0, const int (&nvalid)[SUB],
                                              int lane, int64_t tile0, uint32_t (&cnt)[SUB][VEC]) {
     constexpr int64_t kTile = (int64_t)kWave * VEC * kWavesPerBlock;   // a wave's tiles are a block-row apart
-    constexpr bool SERIAL = (VEC > 1);   // vector paths: one row load in flight per wave
+    // one row load in flight per wave where momentum is written back (read/write mix); the
+    // read-only forms (sign_pack, signSGD step) keep all loads of the group in flight
+    constexpr bool SERIAL = (VEC > 1) && (MOM || SSV_SERIAL_READONLY);
     float gv[U][SUB][VEC];
     float vv[U][SUB][VEC];
     const GT* __restrict__ g = static_cast<const GT*>(a.g);
@@ -85,12 +92,8 @@ __device__ __forceinline__ void worker_group(const StepArgs& a, int m0, int64_t 
                 if constexpr (GUARD) b[c] = (c < nvalid[s]) ? b[c] : 0u;
                 cnt[s][c] += b[c];
             }
-            if (OUT && a.signs_out != nullptr) {
-                uint64_t words[VEC];
-                pack_tile<VEC>(b, words);
-                store_tile_words<VEC>(a.signs_out + (int64_t)m * a.signs_stride, tile0 + s * kWavesPerBlock, a.W, lane,
-                                      words);
-            }
+            if (OUT && a.signs_out != nullptr)
+                pack_store_tile<VEC>(a.signs_out + (int64_t)m * a.signs_stride, tile0 + s * kWavesPerBlock, a.W, lane, b);
         }
     }
 }
@@ -128,11 +131,7 @@ __device__ __forceinline__ void step_tiles(const StepArgs& a, int64_t tile0, int
             vb[c] = (cnt[s][c] >= (uint32_t)a.T) ? 1u : 0u;
             if constexpr (GUARD) vb[c] = (c < nvalid[s]) ? vb[c] : 0u;
         }
-        if (OUT && a.vote_out != nullptr) {
-            uint64_t words[VEC];
-            pack_tile<VEC>(vb, words);
-            store_tile_words<VEC>(a.vote_out, tile0 + s * kWavesPerBlock, a.W, lane, words);
-        }
+        if (OUT && a.vote_out != nullptr) pack_store_tile<VEC>(a.vote_out, tile0 + s * kWavesPerBlock, a.W, lane, vb);
         if constexpr (APPLY) {
             if (nvalid[s] > 0) {
                 XT* xp = static_cast<XT*>(a.x) + j0 + s * kTile;
