@@ -1,0 +1,123 @@
+"""GPU integration checks around the C ABI: caller streams, HIP graph replay, and the paper's toy
+problem driven end to end through the fused step."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as ora
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def sv():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU")
+    import paper_1810_05291_amd as sv_
+    sv_.load_library()
+    return sv_
+
+
+def _host(t):
+    return np.ascontiguousarray(wl.to_numpy(t.contiguous()))
+
+
+def test_calls_follow_the_callers_stream(sv):
+    # work enqueued on a side stream (default priority) is ordered with that stream's other work
+    M, d = 7, 300_001
+    g = wl.gaussian((M, d), 1.0, seed=1, device=DEV)
+    x = wl.gaussian((d,), 0.02, seed=2, device=DEV)
+    x_ref = _host(x).copy()
+    side = torch.cuda.Stream(device=DEV)
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        signs = sv.sign_pack(g)
+        vote = sv.majority_vote(signs, d)
+        sv.apply_sign_update(x, vote, 1e-3)
+        sv.vote_apply(signs, d, x, 1e-3)
+    side.synchronize()
+    ora.signum_step(_host(g), None, 0.0, x_ref, 1e-3)
+    ora.signum_step(_host(g), None, 0.0, x_ref, 1e-3)
+    assert np.array_equal(_host(x), x_ref)
+
+
+def test_fused_step_replays_in_a_hip_graph(sv):
+    # the library only launches kernels (no allocation, no memset), so a call can be captured;
+    # every replay is one more optimiser step and must match eager execution bit for bit
+    M, d = 15, 200_003
+    mu = wl.shared_mean(d, seed=3, device=DEV)
+    g = wl.worker_gradients(mu, M, 0, base_seed=40)
+    x_g = wl.gaussian((d,), 0.02, seed=5, device=DEV)
+    v_g = torch.zeros((M, d), device=DEV)
+    x_e, v_e = x_g.clone(), v_g.clone()
+    vote_g = torch.zeros((sv.words_for(d),), dtype=torch.int64, device=DEV)
+    vote_e = torch.zeros_like(vote_g)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream(device=DEV)
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            sv.signum_step(g, v_g, 0.9, x_g, 1e-4, vote_out=vote_g)
+    torch.cuda.synchronize()
+    # capture does not execute: state is still the initial one
+    assert torch.equal(x_g, x_e) and torch.equal(v_g, v_e)
+    x_ref, v_ref = _host(x_e).copy(), np.zeros((M, d), np.float32)
+    g_h = _host(g)
+    for step in range(4):
+        graph.replay()
+        sv.signum_step(g, v_e, 0.9, x_e, 1e-4, vote_out=vote_e)       # eager work between replays
+        torch.cuda.synchronize()
+        vote_ref, _ = ora.signum_step(g_h, v_ref, 0.9, x_ref, 1e-4)
+        assert torch.equal(x_g, x_e) and torch.equal(v_g, v_e) and torch.equal(vote_g, vote_e), f"replay {step}"
+        assert np.array_equal(_host(x_g), x_ref) and np.array_equal(_host(vote_g), vote_ref)
+
+
+def _quadratic_run(sv, M, adversaries, steps, mode, seed):
+    """signSGD with majority vote on f(x) = |x|^2 / 2 in 1000 dimensions, N(0,1) noise on every
+    gradient component (the paper's toy experiment, first figure); returns the loss curve and checks the
+    trajectory against the oracle at every step."""
+    d, lr = 1000, 1e-2
+    x = wl.gaussian((d,), 1.0, seed=seed, device=DEV)
+    x_ref = _host(x).copy()
+    flip = [1] * adversaries + [0] * (M - adversaries)
+    losses = [float(0.5 * (x_ref.astype(np.float64) ** 2).sum())]
+    for k in range(steps):
+        noise = wl.gaussian((M, d), 1.0, seed=seed + 1 + k, device=DEV)
+        g = (x[None, :] + noise).contiguous()                       # gradient of the quadratic is x
+        g_h = _host(g)
+        if mode == "invert":
+            sv.signum_step(g, None, 0.0, x, lr, worker_flip=flip)
+            ora.signum_step(g_h, None, 0.0, x_ref, lr, worker_flip=flip)
+        else:                                                        # adversaries send random signs
+            signs = sv.sign_pack(g)
+            rnd = wl.random_words((adversaries, signs.shape[1]), seed=seed + 10_000 + k, device=DEV)
+            signs[:adversaries] = rnd
+            sv.vote_apply(signs, d, x, lr)
+            s_h = ora.sign_pack(g_h)
+            s_h[:adversaries] = _host(rnd)
+            ora.vote_apply(s_h, d, x_ref, lr)
+        torch.cuda.synchronize()
+        assert np.array_equal(_host(x), x_ref), f"trajectory left the oracle's at step {k}"
+        losses.append(float(0.5 * (x_ref.astype(np.float64) ** 2).sum()))
+    return losses
+
+
+def test_toy_quadratic_converges_and_degrades_gracefully(sv):
+    M, steps = 27, 300
+    clean = _quadratic_run(sv, M, 0, steps, "invert", seed=100)
+    some = _quadratic_run(sv, M, 9, steps, "invert", seed=100)        # a third of the workers invert
+    many = _quadratic_run(sv, M, 13, steps, "invert", seed=100)       # 48%: still a (thin) honest majority
+    rnd = _quadratic_run(sv, M, 13, steps, "random", seed=100)
+    print(f"toy quadratic, loss after {steps} steps from {clean[0]:.1f}: no adversaries {clean[-1]:.2f}, "
+          f"9/27 inverting {some[-1]:.2f}, 13/27 inverting {many[-1]:.2f}, 13/27 random {rnd[-1]:.2f}", flush=True)
+    assert clean[-1] < 0.05 * clean[0]
+    assert some[-1] < 0.2 * some[0]
+    assert many[-1] < many[0]                      # still descends with 48% adversaries
+    assert rnd[-1] < 0.2 * rnd[0]                  # random adversaries hurt less than inverting ones
+    assert clean[-1] <= some[-1] <= many[-1]
+    # with an adversarial majority the vote points uphill
+    lost = _quadratic_run(sv, M, 14, 60, "invert", seed=100)
+    assert lost[-1] > lost[0]
