@@ -266,20 +266,21 @@ hipError_t launch_vote(const VoteArgs& a_in, int x_dt, bool rows16, bool x_vecto
 // A lane owns XV consecutive coordinates and reads the byte of the vote that holds their bits.
 template <typename XT, int XV>
 __global__ __launch_bounds__(kBlock) void apply_kernel(ApplyArgs a) {
-    const int64_t j0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * XV;
-    if (j0 >= a.d) return;
-    const int64_t left = a.d - j0;
-    const int n = left >= XV ? XV : (int)left;
     const uint8_t* __restrict__ vb = reinterpret_cast<const uint8_t*>(a.vote);
-    const uint32_t bits = (uint32_t)vb[j0 >> 3] >> (j0 & 7);
-    apply_piece<XT, XV>(static_cast<XT*>(a.x) + j0, n, bits, a.lr, a.wd);
+    const int64_t step = (int64_t)gridDim.x * kBlock * XV;      // one pass unless the grid was capped
+    for (int64_t j0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * XV; j0 < a.d; j0 += step) {
+        const int64_t left = a.d - j0;
+        const int n = left >= XV ? XV : (int)left;
+        const uint32_t bits = (uint32_t)vb[j0 >> 3] >> (j0 & 7);
+        apply_piece<XT, XV>(static_cast<XT*>(a.x) + j0, n, bits, a.lr, a.wd);
+    }
 }
 
 template <typename XT, int XV>
 static hipError_t launch_apply_one(const ApplyArgs& a, hipStream_t s) {
     int64_t threads = (a.d + XV - 1) / XV;
     int64_t grid = (threads + kBlock - 1) / kBlock;
-    if (grid > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    if (grid > 0x40000000LL) grid = 0x40000000LL;               // the kernel strides over the rest
     hipLaunchKernelGGL((apply_kernel<XT, XV>), dim3((unsigned)grid), dim3(kBlock), 0, s, a);
     return hipGetLastError();
 }

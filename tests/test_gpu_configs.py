@@ -256,3 +256,50 @@ def test_config5_large_bf16_step_streamed_chunks(sv):
     changed = (_host(x[: 1 << 22]) != x_before).mean()
     _log(f"config5: fraction of bf16 weights that moved in 2 steps of lr = 1e-5 (first 2^22): {changed:.4f} "
          f"(a step smaller than half an ulp of the weight rounds back to the same bf16 value)")
+
+
+# ------------------------------------------------------------------ indices beyond 2^31
+
+@pytest.mark.timeout(600)
+def test_more_than_2_pow_31_coordinates(sv):
+    # 64-bit indexing: a vector longer than 2^31 elements with a ragged end, checked at the far end
+    M, d, beta, lr = 2, (1 << 31) + 100_003, 0.5, 1e-3
+    free, _ = torch.cuda.mem_get_info()
+    if free < 40 << 30:
+        pytest.fail("needs 40 GiB of HBM")
+    g = torch.empty((M, d), dtype=torch.bfloat16, device=DEV)
+    v = torch.zeros((M, d), dtype=torch.float32, device=DEV)
+    x = torch.empty((d,), dtype=torch.bfloat16, device=DEV)
+    step_sz = 1 << 28
+    for c0 in range(0, d, step_sz):
+        c1 = min(d, c0 + step_sz)
+        for m in range(M):
+            g[m, c0:c1] = wl.gaussian((c1 - c0,), 1.0, seed=c0 // step_sz * 10 + m, device=DEV).to(torch.bfloat16)
+        x[c0:c1] = wl.gaussian((c1 - c0,), 0.02, seed=1000 + c0 // step_sz, device=DEV).to(torch.bfloat16)
+    W = sv.words_for(d)
+    vote = torch.empty((W,), dtype=torch.int64, device=DEV)
+    signs = torch.empty((M, W), dtype=torch.int64, device=DEV)
+    n = 70_001
+    probes = [0, (1 << 31) - 33_024, d - n]          # the middle one straddles index 2^31
+    before = {j0: (_host(x[j0:j0 + n]).copy(), np.zeros((M, n), np.float32)) for j0 in probes}
+    sv.signum_step(g, v, beta, x, lr, vote_out=vote, signs_out=signs)
+    vote2 = sv.majority_vote(signs, d)
+    torch.cuda.synchronize()
+    assert torch.equal(vote, vote2)
+    for j0 in probes:
+        x_ref, v_ref = before[j0]
+        vote_ref, signs_ref = ora.signum_step(_host(g[:, j0:j0 + n]), v_ref, beta, x_ref, lr, want_signs=True)
+        assert np.array_equal(_host(v[:, j0:j0 + n]), v_ref), f"momentum differs at {j0}"
+        assert np.array_equal(_host(x[j0:j0 + n]), x_ref), f"weights differ at {j0}"
+        if j0 % 64 == 0:                          # word-aligned probes: compare packed words directly
+            w0, nw = j0 // 64, n // 64
+            assert np.array_equal(_host(vote[w0:w0 + nw]), vote_ref[:nw])
+            assert np.array_equal(_host(signs[:, w0:w0 + nw]), signs_ref[:, :nw])
+    # the ragged last word: bits past d are zero
+    last_bits = d - 64 * (W - 1)
+    assert int(_host(vote[W - 1:])[0]) >> last_bits == 0
+    assert (_host(signs[:, W - 1:]) >> np.uint64(last_bits) == 0).all()
+    tail0 = 64 * (W - 1)
+    vote_tail, _ = ora.signum_step(_host(g[:, tail0:]), np.zeros((M, d - tail0), np.float32), beta,
+                                   _host(x[tail0:]).copy() * 0, lr)
+    assert int(_host(vote[W - 1:])[0]) == int(vote_tail[0])
