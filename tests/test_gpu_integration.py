@@ -121,3 +121,48 @@ def test_toy_quadratic_converges_and_degrades_gracefully(sv):
     # with an adversarial majority the vote points uphill
     lost = _quadratic_run(sv, M, 14, 60, "invert", seed=100)
     assert lost[-1] > lost[0]
+
+
+_VARIANT_SCRIPT = r"""
+import numpy as np, torch, sys
+sys.path.insert(0, %r)
+import paper_1810_05291_amd as sv, oracle as ora, workloads as wl
+dev = "cuda:0"
+for (M, d, gdt) in ((15, 100_003, torch.float32), (31, 70_001, torch.bfloat16), (3, 17, torch.float32)):
+    mu = wl.shared_mean(d, seed=1, device=dev)
+    x = wl.gaussian((d,), 0.02, seed=2, device=dev)
+    v = torch.zeros((M, d), device=dev)
+    x_ref, v_ref = wl.to_numpy(x).copy(), np.zeros((M, d), np.float32)
+    W = sv.words_for(d)
+    for step in range(2):
+        g = wl.worker_gradients(mu, M, step, base_seed=9, dtype=gdt)
+        vote = torch.empty((W,), dtype=torch.int64, device=dev)
+        signs = torch.empty((M, W), dtype=torch.int64, device=dev)
+        sv.signum_step(g, v, 0.9, x, 1e-4, vote_out=vote, signs_out=signs)
+        x2 = x.clone(); sv.vote_apply(signs, d, x2, 1e-4)
+        torch.cuda.synchronize()
+        vote_ref, signs_ref = ora.signum_step(wl.to_numpy(g), v_ref, 0.9, x_ref, 1e-4, want_signs=True)
+        assert np.array_equal(wl.to_numpy(signs), signs_ref) and np.array_equal(wl.to_numpy(vote), vote_ref)
+        assert np.array_equal(wl.to_numpy(v), v_ref) and np.array_equal(wl.to_numpy(x), x_ref)
+        x_ref2 = x_ref.copy(); ora.apply_sign_update(x_ref2, vote_ref, 1e-4)
+        assert np.array_equal(wl.to_numpy(x2), x_ref2)
+        sv.signum_step(g, v, 0.9, x, 1e-4)                    # lean form
+        torch.cuda.synchronize()
+        ora.signum_step(wl.to_numpy(g), v_ref, 0.9, x_ref, 1e-4)
+        assert np.array_equal(wl.to_numpy(v), v_ref) and np.array_equal(wl.to_numpy(x), x_ref)
+print("variant ok")
+"""
+
+
+@pytest.mark.parametrize("env", [{"SSV_TUNE_STEP_SUB": "1"}, {"SSV_TUNE_STEP_SUB": "2"}, {"SSV_TUNE_XCD_REMAP": "1"},
+                                 {"SSV_TUNE_STEP_SUB": "2", "SSV_TUNE_XCD_REMAP": "1"}])
+def test_launch_shape_knobs_keep_parity(env):
+    # the SSV_TUNE_* knobs are read once per process, so each setting runs in a child process
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    child_env = dict(os.environ, **env)
+    r = subprocess.run([sys.executable, "-c", _VARIANT_SCRIPT % root], env=child_env, capture_output=True, text=True,
+                       timeout=240)
+    assert r.returncode == 0 and "variant ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
