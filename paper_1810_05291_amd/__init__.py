@@ -21,3 +21,4 @@ from .binding import (  # noqa: F401
     status_string,
     version,
 )
+from .optim import FlatLayout, SignumMajorityVote  # noqa: F401,E402

@@ -1,0 +1,82 @@
+"""Flat-vector plumbing for real models: the paper's "fusing together smaller tensors" (Section 4).
+
+The library works on one flat vector of d coordinates.  A model has many parameter tensors; this
+module lays them out back to back in one flat buffer ONCE, hands out views for the parameters and
+for each simulated worker's gradients, and calls the fused step on the flat buffers.  No copies are
+made per step, and every step is one kernel launch however many tensors the model has.
+
+Only memory plumbing lives here; all arithmetic is in libsignvote.
+"""
+import math
+
+import torch
+
+from . import binding as _b
+
+
+class FlatLayout:
+    """Offsets of a list of tensor shapes inside one flat vector (back to back, no padding: the
+    kernels handle any d, and padding coordinates would be updated like real ones)."""
+
+    def __init__(self, shapes):
+        self.shapes = [tuple(int(s) for s in shape) for shape in shapes]
+        self.sizes = [int(math.prod(s)) for s in self.shapes]
+        self.offsets = []
+        off = 0
+        for n in self.sizes:
+            self.offsets.append(off)
+            off += n
+        self.numel = off
+        if self.numel < 1:
+            raise ValueError("empty layout")
+
+    def row_stride(self, align_elems=32):
+        """Row stride for [M][stride] buffers: numel rounded up so that every row starts on a 128-byte boundary."""
+        return ((self.numel + align_elems - 1) // align_elems) * align_elems
+
+    def views(self, flat):
+        """One view per tensor into the 1-D buffer `flat` (at least numel elements)."""
+        if flat.dim() != 1 or flat.numel() < self.numel:
+            raise ValueError("flat buffer too small")
+        return [flat[o:o + n].view(s) for o, n, s in zip(self.offsets, self.sizes, self.shapes)]
+
+
+class SignumMajorityVote:
+    """Signum with majority vote (Algorithm 1) for M simulated workers on one GPU.
+
+    params            list of views into the flat weight vector (update happens in place)
+    grads[m]          list of views into worker m's flat gradient row: write gradients there
+    step()            one fused launch: momentum, sign, vote, update for all workers
+    """
+
+    def __init__(self, shapes, num_workers, lr=1e-4, beta=0.9, weight_decay=0.0, device="cuda:0",
+                 param_dtype=torch.float32, grad_dtype=torch.float32):
+        if num_workers < 1:
+            raise ValueError("need at least one worker")
+        self.layout = FlatLayout(shapes)
+        self.M = int(num_workers)
+        self.lr, self.beta, self.weight_decay = float(lr), float(beta), float(weight_decay)
+        d = self.layout.numel
+        stride_g = self.layout.row_stride(32 if grad_dtype == torch.float32 else 64)
+        stride_v = self.layout.row_stride(32)
+        self.x = torch.zeros((d,), dtype=param_dtype, device=device)
+        self.g = torch.zeros((self.M, stride_g), dtype=grad_dtype, device=device)[:, :d]
+        self.v = torch.zeros((self.M, stride_v), dtype=torch.float32, device=device)[:, :d] if self.beta > 0 else None
+        self.params = self.layout.views(self.x)
+        self.grads = [self.layout.views(self.g[m]) for m in range(self.M)]
+        self.steps = 0
+
+    def step(self, worker_flip=None, vote_out=None):
+        _b.signum_step(self.g, self.v, self.beta, self.x, self.lr, self.weight_decay, vote_out=vote_out,
+                       worker_flip=worker_flip)
+        self.steps += 1
+
+    def state_dict(self):
+        """Everything Algorithm 1 carries between iterations: x, the per-worker momenta, the step count."""
+        return {"x": self.x.clone(), "v": None if self.v is None else self.v.clone(), "steps": self.steps}
+
+    def load_state_dict(self, state):
+        self.x.copy_(state["x"])
+        if self.v is not None:
+            self.v.copy_(state["v"])
+        self.steps = int(state["steps"])

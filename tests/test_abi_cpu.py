@@ -93,3 +93,19 @@ def test_product_package_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower().replace("no cpu fallback", ""), f
+
+
+def test_flat_layout_offsets():
+    from paper_1810_05291_amd import FlatLayout
+    import torch
+    lay = FlatLayout([(3, 5), (7,), (2, 2, 2), ()])
+    assert lay.sizes == [15, 7, 8, 1] and lay.offsets == [0, 15, 22, 30] and lay.numel == 31
+    assert lay.row_stride() == 32 and lay.row_stride(64) == 64
+    flat = torch.arange(31, dtype=torch.float32)
+    views = lay.views(flat)
+    assert [tuple(v.shape) for v in views] == [(3, 5), (7,), (2, 2, 2), ()]
+    assert views[1][0].item() == 15 and views[3].item() == 30
+    views[2].zero_()
+    assert flat[22:30].abs().sum().item() == 0 and flat[21].item() == 21    # views alias the flat buffer
+    with pytest.raises(ValueError):
+        lay.views(torch.zeros(30))

@@ -166,3 +166,51 @@ def test_launch_shape_knobs_keep_parity(env):
     r = subprocess.run([sys.executable, "-c", _VARIANT_SCRIPT % root], env=child_env, capture_output=True, text=True,
                        timeout=240)
     assert r.returncode == 0 and "variant ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
+
+
+def test_small_model_trains_through_the_flat_layout(sv):
+    # a two-layer network on synthetic regression data, 5 simulated workers with their own mini-batches;
+    # many parameter tensors, one flat vector, one launch per step; trajectory followed by the oracle
+    torch.manual_seed(0)
+    M, steps = 5, 60
+    shapes = [(64, 20), (64,), (1, 64), (1,)]
+    opt = sv.SignumMajorityVote(shapes, M, lr=2e-3, beta=0.9, device=DEV)
+    for p, std in zip(opt.params, (0.2, 0.0, 0.1, 0.0)):
+        p.copy_(torch.randn(p.shape, device=DEV) * std)
+    params = [p.detach().requires_grad_() for p in opt.params]        # leaves that alias the flat vector
+    w_true = torch.randn(20, device=DEV)
+
+    def batch(seed, n=64):
+        gen = torch.Generator(device=DEV).manual_seed(seed)
+        xb = torch.randn(n, 20, device=DEV, generator=gen)
+        yb = torch.tanh(xb @ w_true)[:, None] + 0.05 * torch.randn(n, 1, device=DEV, generator=gen)
+        return xb, yb
+
+    def loss_fn(xb, yb):
+        h = torch.relu(xb @ params[0].T + params[1])
+        return ((h @ params[2].T + params[3] - yb) ** 2).mean()
+
+    x_ref = _host(opt.x).copy()
+    v_ref = np.zeros((M, opt.layout.numel), np.float32)
+    xe, ye = batch(10_000, 2048)
+    first = loss_fn(xe, ye).item()
+    for k in range(steps):
+        for m in range(M):
+            grads = torch.autograd.grad(loss_fn(*batch(1 + k * M + m)), params)
+            for dst, src in zip(opt.grads[m], grads):
+                dst.copy_(src)
+        opt.step()
+        torch.cuda.synchronize()
+        ora.signum_step(_host(opt.g), v_ref, 0.9, x_ref, 2e-3)
+        assert np.array_equal(_host(opt.x), x_ref), f"step {k}"
+    assert np.array_equal(_host(opt.v), v_ref)
+    last = loss_fn(xe, ye).item()
+    print(f"small model: evaluation loss {first:.4f} -> {last:.4f} in {steps} fused steps", flush=True)
+    assert last < 0.5 * first
+    # checkpoint / resume: state is x, the momenta and the step count
+    state = opt.state_dict()
+    opt.step()
+    after = opt.x.clone()
+    opt.load_state_dict(state)
+    opt.step()
+    assert torch.equal(opt.x, after)
