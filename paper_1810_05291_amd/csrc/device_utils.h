@@ -18,7 +18,7 @@ __device__ __forceinline__ void stream_store(V* p, V v) { __builtin_nontemporal_
 // load of the fused step it keeps ONE load per wave in flight: with 16-20 waves per CU that is
 // already enough bytes in flight to cover HBM latency, and on MI355X the fused step then runs
 // about 10% faster than with 16 loads per wave queued up (deep per-wave queues lower the
-// sustained HBM rate of this 30-stream read/write mix; measured, see the design notes).
+// sustained HBM rate of this 30-stream read/write mix: 5.3 vs 5.8-6.0 TB/s measured).
 __device__ __forceinline__ void drain_memory_ops() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // ---- loads: VEC consecutive elements starting at p, widened to fp32 ------------------------
