@@ -272,7 +272,8 @@ def test_step_tiny_config_signsgd(sv):
 
 @pytest.mark.parametrize("M,d,pad,x_off", [(1, 1, 0, 0), (2, 64, 0, 0), (3, 257, 0, 0), (15, 100003, 0, 0),
                                             (15, 100003, 1, 0), (15, 100000, 0, 1), (31, 70001, 3, 0),
-                                            (16, 4096, 0, 0), (40, 3000, 0, 0)])
+                                            (16, 4096, 0, 0), (40, 3000, 0, 0), (255, 4097, 0, 0),
+                                            (1023, 2049, 0, 0), (1022, 700, 2, 1)])
 def test_step_signum_fp32(sv, M, d, pad, x_off):
     _log(f"signum_step fp32 M={M} d={d} pad={pad} x_off={x_off}")
     nz = _step_case(sv, M, d, torch.float32, torch.float32, 0.9, 0.0, steps=3, pad=pad, x_off=x_off)
