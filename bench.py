@@ -162,7 +162,7 @@ def main():
             n_cpu += 1
         # keep timing (on copies, so the parity state is not disturbed) until about 10 s of CPU work
         xs, vs = x_ref.copy(), v_ref.copy()
-        while t_cpu < 10.0 and n_cpu < 200:
+        while t_cpu < 10.0 and n_cpu < 1000:
             t0 = time.perf_counter()
             ora.signum_step(g_h[n_cpu % len(g_h)], vs, beta, xs, lr)
             t_cpu += time.perf_counter() - t0

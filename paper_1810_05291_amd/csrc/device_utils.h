@@ -1,5 +1,5 @@
 // Device-side helpers: vector loads/stores of fp32 / bf16 runs, the update formula, and the
-// ballot-based packing of per-lane sign bits into the 64-coordinates-per-word message format.
+// packing of per-lane sign bits into the 64-coordinates-per-word message format.
 #pragma once
 #include "common.h"
 

@@ -15,7 +15,7 @@
 // tiles w, w+4, ..: the four waves' accesses of one step form one contiguous 4 KiB run per row,
 // which measures about 6% faster on MI355X than giving each wave SUB adjacent tiles.
 // A lane keeps its coordinates through all M workers, so nothing crosses lanes except the
-// optional ballots.  The kernel is HBM-bound: 12 bytes per worker-coordinate (read g, read v,
+// optional packing.  The kernel is HBM-bound: 12 bytes per worker-coordinate (read g, read v,
 // write v) plus 8 per coordinate for x at fp32.  Per group of U = 2 workers a wave reads its
 // 2*U*SUB row pieces one at a time (each load waits for the one before), then computes and issues
 // the U*SUB momentum stores back to back: a read phase and a write burst per group.
