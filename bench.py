@@ -72,6 +72,14 @@ def time_launches(torch, fn, iters, warmup=2):
 def other_kernels(torch, sv, wl, dev):
     """Secondary measurements: the kernels that are not the headline, at their own workloads."""
     out = {}
+    # yardstick: the library's plain streaming copy (1:1 read/write), 1.5 GB like one gradient set
+    src = wl.gaussian((15 * 25_557_056,), 1.0, seed=1, device=dev)
+    dst = torch.empty_like(src)
+    ms = time_launches(torch, lambda i: sv.bench_copy(src, dst), 20)
+    b = 2.0 * src.numel() * 4
+    out["stream_copy_1.5GB"] = {"ms": ms, "GB/s": b / ms / 1e6, "frac": b / ms / 1e6 / HBM_PEAK_GBS,
+                                "note": "plain 16-byte non-temporal copy, bytes read + written"}
+    del src, dst
     # packed majority vote, d = 2^30, M = 255 (uniform random bits: the kernel is data-oblivious)
     M, d = 255, 1 << 30
     W = sv.words_for(d)
@@ -128,9 +136,10 @@ def main():
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
         for _ in range(3):
-            dst.copy_(src)
+            sv.bench_copy(src, dst)          # ssv::copy_kernel: exactly 1 GiB read + 1 GiB written per launch
         torch.cuda.synchronize()
-        print(json.dumps({"copy_calibration": "3 copies", "bytes_read_each": src.numel() * 4,
+        assert torch.equal(src, dst)
+        print(json.dumps({"copy_calibration": "3 launches of ssv::copy_kernel", "bytes_read_each": src.numel() * 4,
                           "bytes_written_each": src.numel() * 4}))
         return
     M, d, K, Wm = args.workers, args.d, args.steps, args.warmup

@@ -20,5 +20,6 @@ from .binding import (  # noqa: F401
     signum_step,
     status_string,
     version,
+    bench_copy,
 )
 from .optim import FlatLayout, SignumMajorityVote  # noqa: F401,E402

@@ -28,6 +28,7 @@ _SIGNATURES = {
     "ssv_vote_apply": [_c_p, _c_int, _c_i64, _c_i64, _c_p, _c_int, _c_f, _c_f, _c_p, _c_p],
     "ssv_signum_step": [_c_p, _c_int, _c_p, _c_int, _c_i64, _c_i64, _c_i64, _c_f, _c_p, _c_int, _c_f, _c_f,
                         _c_p, _c_p, _c_i64, _c_p, _c_p],
+    "ssv_bench_copy": [_c_p, _c_p, _c_i64, _c_p],
 }
 
 
@@ -199,3 +200,13 @@ def signum_step(g, v, beta, x, lr, weight_decay=0.0, vote_out=None, signs_out=No
                                           float(lr), float(weight_decay), _ptr(vote_out), _ptr(signs_out), ss,
                                           ctypes.cast(flip, _c_p) if flip is not None else None, _stream(dev)))
     return x
+
+
+def bench_copy(src, dst):
+    """dst <- src with the library's plain streaming copy kernel (bandwidth yardstick, counter calibration)."""
+    dev = _dev(src, dst)
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes or not src.is_contiguous() or not dst.is_contiguous():
+        raise ValueError("src and dst must be contiguous and of equal size")
+    _check("ssv_bench_copy", load_library().ssv_bench_copy(_ptr(src), _ptr(dst), nbytes, _stream(dev)))
+    return dst

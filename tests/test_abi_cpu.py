@@ -7,7 +7,7 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "signvote.h")
+HEADERS = [os.path.join(ROOT, "include", "signvote.h"), os.path.join(ROOT, "include", "signvote_bench.h")]
 
 
 @pytest.fixture(scope="module")
@@ -20,15 +20,17 @@ def lib():
 
 
 def _declared_symbols():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(ssv_[a-z_]+)\s*\(", text)))
+    names = set()
+    for header in HEADERS:
+        text = re.sub(r"/\*.*?\*/", "", open(header).read(), flags=re.S)
+        names |= set(re.findall(r"\b(ssv_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_symbols_are_exported(lib):
     names = _declared_symbols()
     assert {"ssv_sign_pack", "ssv_signum_momentum_pack", "ssv_majority_vote", "ssv_apply_sign_update",
-            "ssv_vote_apply", "ssv_signum_step", "ssv_status_string", "ssv_version"} <= set(names)
+            "ssv_vote_apply", "ssv_signum_step", "ssv_status_string", "ssv_version", "ssv_bench_copy"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in signvote.h but not exported"
 
@@ -77,6 +79,9 @@ def test_argument_validation_needs_no_device(lib):
     assert lib.ssv_signum_step(P, 0, None, 3, 1000, 1000, 0, 0.9, P, 0, 1e-3, 0.0, None, None, 0, None, None) == -5
     assert lib.ssv_signum_step(P, 0, P, 3, 1000, 1000, 1000, 0.9, None, 0, 1e-3, 0.0, None, None, 0, None, None) == -1
     assert lib.ssv_signum_step(P, 0, P, 3, 1000, 1000, 1000, 0.9, P, 0, 1e-3, 0.0, None, P, 3, None, None) == -2
+    assert lib.ssv_bench_copy(None, P, 1024, None) == -1
+    assert lib.ssv_bench_copy(P, P + 4096, 1000, None) == -2
+    assert lib.ssv_bench_copy(P + 8, P + 4096, 1024, None) == -3
 
 
 def test_binding_refuses_cpu_tensors():

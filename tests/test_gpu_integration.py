@@ -44,6 +44,16 @@ def test_calls_follow_the_callers_stream(sv):
     assert np.array_equal(_host(x), x_ref)
 
 
+def test_bench_copy_copies(sv):
+    src = wl.gaussian((1_000_000,), 1.0, seed=8, device=DEV)
+    dst = torch.zeros(1_000_004, device=DEV)
+    sv.bench_copy(src, dst[:1_000_000])
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:1_000_000], src) and (dst[1_000_000:] == 0).all()
+    with pytest.raises(sv.SignvoteError):
+        sv.bench_copy(src[1:5], dst[1:5])            # not 16-byte aligned
+
+
 def test_fused_step_replays_in_a_hip_graph(sv):
     # the library only launches kernels (no allocation, no memset), so a call can be captured;
     # every replay is one more optimiser step and must match eager execution bit for bit
