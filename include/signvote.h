@@ -63,7 +63,7 @@ typedef enum {
 } ssv_status;
 
 /*
- * Sign compression (Algorithm 1, "push sign(v_m)"; Section 4, bit-packing of sign tensors).
+ * Sign compression (Algorithm 1, the worker's send line; Section 4, bit-packing of sign tensors).
  * For each of the M rows of x:  signs[m][w] bit i = (x[m][64 w + i] >= 0).
  *   x      device, M rows of d elements of type dt, row stride x_row_stride elements (>= d)
  *   signs  device, M rows of ceil(d/64) uint64 words, row stride signs_row_stride_words (>= ceil(d/64))
@@ -72,7 +72,7 @@ int ssv_sign_pack(const void* x, int dt, int M, int64_t d, int64_t x_row_stride,
                   uint64_t* signs, int64_t signs_row_stride_words, void* stream);
 
 /*
- * Worker side of Signum (Algorithm 1, "update momentum" then "push sign(v_m)").
+ * Worker side of Signum (Algorithm 1, the worker's momentum line, then its send line).
  * v[m] <- (1 - beta) g[m] + beta v[m] in place (fp32), signs[m] = packed (v[m] >= 0).
  *   g      device, M rows of d elements of type g_dt, row stride g_row_stride
  *   v      device, M rows of d fp32, row stride v_row_stride, read and written
@@ -83,7 +83,7 @@ int ssv_signum_momentum_pack(const void* g, int g_dt, float* v, int M, int64_t d
                              uint64_t* signs, int64_t signs_row_stride_words, void* stream);
 
 /*
- * Server side (Algorithm 1, "aggregate sign momenta" and "broadcast majority vote"):
+ * Server side (Algorithm 1, the server's two lines: sum the sign vectors, send back the sign of the sum):
  * vote[w] bit i = [ #{m : signs[m][w] bit i set} >= (M + 1) / 2 ], i.e. sign(sum_m +-1) with
  * ties to +1.  Padding bits of the inputs are ignored; those of `vote` are written 0.
  *   signs  device, M packed rows;  vote  device, ceil(d/64) words
@@ -92,7 +92,7 @@ int ssv_majority_vote(const uint64_t* signs, int M, int64_t d, int64_t signs_row
                       uint64_t* vote, void* stream);
 
 /*
- * Parameter update (Algorithm 1, "update parameters"): x <- x - lr (s + weight_decay x), s = +1
+ * Parameter update (Algorithm 1, the last line: every worker updates x): x <- x - lr (s + weight_decay x), s = +1
  * where the vote bit is set, else -1.  In place on x (d elements of type x_dt).
  */
 int ssv_apply_sign_update(void* x, int x_dt, int64_t d, const uint64_t* vote,
@@ -110,7 +110,7 @@ int ssv_vote_apply(const uint64_t* signs, int M, int64_t d, int64_t signs_row_st
 /*
  * One whole iteration of Algorithm 1 for all M workers in one kernel: momentum, sign, vote and
  * update; signs and vote counts stay in registers.
- *   v == NULL    signSGD ("Setting beta = 0 yields signSGD"): no momentum state is read or
+ *   v == NULL    signSGD (the caption of Algorithm 1: beta = 0 turns Signum into signSGD): no momentum state is read or
  *                written and the sign is taken of g itself; beta must then be 0.
  *   v != NULL    Signum: v is updated in place as in ssv_signum_momentum_pack.
  *   vote_out     optional, ceil(d/64) words: the packed vote.

@@ -88,14 +88,14 @@ void ora_f32_to_bf16(const float *x, int64_t n, uint16_t *out) {
     for (int64_t i = 0; i < n; ++i) out[i] = f32_to_bf16_bits(x[i]);
 }
 
-/* ---------- sign (Algorithm 1, "push sign(v_m)"; reading R1) ---------- */
+/* ---------- sign (Algorithm 1, the worker's send line; reading R1) ---------- */
 
 void ora_sign_f32(const float *x, int64_t n, int8_t *s) {
 #pragma omp parallel for schedule(static)
     for (int64_t i = 0; i < n; ++i) s[i] = (x[i] >= 0.0f) ? 1 : -1;
 }
 
-/* ---------- 1-bit message format (Section 4 "bit-pack a sign tensor"; R3) ---------- */
+/* ---------- 1-bit message format (Section 4, bit-packing of sign tensors; R3) ---------- */
 
 void ora_pack_signs(const int8_t *s, int64_t d, uint64_t *words) {
     int64_t W = (d + 63) / 64;
@@ -115,7 +115,7 @@ void ora_unpack_signs(const uint64_t *words, int64_t d, int8_t *s) {
     for (int64_t j = 0; j < d; ++j) s[j] = ((words[j / 64] >> (j % 64)) & 1u) ? 1 : -1;
 }
 
-/* ---------- momentum (Algorithm 1, "update momentum") ---------- */
+/* ---------- momentum (Algorithm 1, the worker's momentum line) ---------- */
 
 void ora_momentum_f32(const float *g, float *v, int64_t n, float beta) {
     const float omb = 1.0f - beta;
@@ -264,7 +264,7 @@ int ora_vote_apply(const uint64_t *signs, int M, int64_t d, int64_t signs_row_st
 /*
  * One whole iteration of Algorithm 1 for all M workers.
  *   v == NULL (then beta must be 0)  ->  signSGD: no momentum state, the sign is taken of
- *                               the gradient itself ("Setting beta = 0 yields signSGD").
+ *                               the gradient itself (caption of Algorithm 1: beta = 0 gives signSGD).
  *                               With v given, the momentum line runs as written for any beta.
  *   worker_flip[m] != 0     ->  worker m transmits the negation of its sign vector
  *                               (the sign-inverting adversary of Definition 1 / Section 4.1);

@@ -116,7 +116,7 @@ __device__ __forceinline__ void store_vals_guarded(T* __restrict__ p, int n, con
     }
 }
 
-// ---- x <- x - lr (s + wd x), s = +1 if plus else -1 (Algorithm 1, "update parameters") ------
+// ---- x <- x - lr (s + wd x), s = +1 if plus else -1 (Algorithm 1, the update line) ------
 __device__ __forceinline__ float sign_update(float x, bool plus, float lr, float wd) {
     if (wd == 0.0f) return x + (plus ? -lr : lr);
     float t = fmaf(wd, x, plus ? 1.0f : -1.0f);

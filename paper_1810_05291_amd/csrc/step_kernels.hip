@@ -1,10 +1,10 @@
 // Gradient-side kernels: sign compression, worker momentum, and the whole fused iteration of
-// Algorithm 1 ("Signum with majority vote").  One templated kernel serves all three entry points:
-//   MOM    v <- (1-beta) g + beta v  in place            ("update momentum")
-//   sign   bit = (value >= 0), optionally flipped        ("push sign(v_m)")
+// Algorithm 1 (Signum with majority vote).  One templated kernel serves all three entry points:
+//   MOM    v <- (1-beta) g + beta v  in place            (worker's momentum line)
+//   sign   bit = (value >= 0), optionally flipped        (worker's send line)
 //   count  per-coordinate count of set bits over the M workers, kept in registers
-//          ("aggregate sign momenta"); vote bit = [count >= (M+1)/2]
-//   APPLY  x <- x - lr (vote + wd x)                      ("update parameters")
+//          (server's sum line); vote bit = [count >= (M+1)/2]  (server's sign-of-sum line)
+//   APPLY  x <- x - lr (vote + wd x)                      (the update line)
 // Packed signs / packed vote are optional outputs (ballot at one coordinate per lane, a DPP
 // merge of 4-bit lane groups at four).
 //

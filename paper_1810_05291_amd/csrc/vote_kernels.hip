@@ -1,5 +1,5 @@
-// Server-side kernels on packed sign rows: the majority vote (Algorithm 1, "aggregate sign
-// momenta" + "broadcast majority vote"), optionally fused with the parameter update, and the
+// Server-side kernels on packed sign rows: the majority vote (Algorithm 1, the server's sum and
+// sign-of-sum lines), optionally fused with the parameter update, and the
 // stand-alone update from a packed vote.
 //
 // The vote never expands to per-coordinate integers.  A lane holds PW 32-bit slices of the row

@@ -1,4 +1,5 @@
-"""Flat-vector plumbing for real models: the paper's "fusing together smaller tensors" (Section 4).
+"""Flat-vector plumbing for real models: the tensor fusion that Section 4 of the paper credits with
+a speed-up of compression and communication.
 
 The library works on one flat vector of d coordinates.  A model has many parameter tensors; this
 module lays them out back to back in one flat buffer ONCE, hands out views for the parameters and
