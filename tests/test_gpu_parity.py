@@ -206,18 +206,24 @@ def _step_case(sv, M, d, g_dtype, x_dtype, beta, wd, steps, pad=0, flip=None, mo
     xbuf = wl.gaussian((d + 8,), 0.02, seed=12, device=DEV).to(x_dtype)
     x = xbuf[x_off:x_off + d]
     x_ref = wl.to_numpy(x.contiguous()).copy()
-    v = v_ref = None
+    v = v_ref = vbuf = None
     if momentum:
-        _, v = _strided(M, d, d + pad, torch.float32, fill=0.0)
+        vbuf, v = _strided(M, d, d + pad, torch.float32, fill=0.0)
         v_ref = np.zeros((M, d), np.float32)
     W = sv.words_for(d)
     near_zero = 0
     for step in range(steps):
         g = wl.worker_gradients(mu, M, step, base_seed=500, noise_std=noise, dtype=g_dtype, row_stride=d + pad)
-        vote = torch.full((W,), -1, dtype=torch.int64, device=DEV)
-        signs = torch.full((M, W + 1), -1, dtype=torch.int64, device=DEV)[:, :W]
+        vote_buf = torch.full((W + 2,), -1, dtype=torch.int64, device=DEV)
+        vote = vote_buf[:W]
+        signs_buf = torch.full((M, W + 1), -1, dtype=torch.int64, device=DEV)
+        signs = signs_buf[:, :W]
         sv.signum_step(g, v, beta, x, lr, wd, vote_out=vote, signs_out=signs, worker_flip=flip)
         torch.cuda.synchronize()
+        # nothing is written past the rows: guard words and pad columns keep their fill
+        assert (vote_buf[W:] == -1).all() and (signs_buf[:, W:] == -1).all()
+        if vbuf is not None and pad > 0:
+            assert (vbuf[:, d:] == 0).all()
         g_h = _np_rows(g)
         v_prev = None if v_ref is None else v_ref.copy()
         vote_ref, signs_ref = ora.signum_step(g_h, v_ref, beta, x_ref, lr, wd, want_signs=True, worker_flip=flip)
