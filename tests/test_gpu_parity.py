@@ -349,3 +349,45 @@ def test_argument_errors_leave_buffers_untouched(sv):
     assert lib.ssv_apply_sign_update(x.data_ptr(), 0, d, signs.data_ptr(), float("nan"), 0.0, None) == -5
     torch.cuda.synchronize()
     assert torch.equal(x, x0) and (signs == 7).all()
+
+
+def test_step_randomised_shapes(sv):
+    # seeded sweep over worker counts, lengths, paddings, dtypes and options
+    rng = np.random.default_rng(2024)
+    dtypes = [torch.float32, torch.bfloat16]
+    for case in range(48):
+        M = int(rng.integers(1, 70))
+        d = int(rng.integers(1, 6000))
+        pad = int(rng.choice([0, 0, 1, 3, 4, 8, 29]))
+        g_dt, x_dt = dtypes[int(rng.integers(2))], dtypes[int(rng.integers(2))]
+        momentum = bool(rng.integers(4) > 0)
+        beta = float(rng.choice([0.0, 0.5, 0.9, 0.99])) if momentum else 0.0
+        wd = float(rng.choice([0.0, 0.0, 0.01]))
+        flip = [int(b) for b in rng.integers(0, 2, size=M)] if rng.integers(3) == 0 else None
+        x_off = int(rng.choice([0, 0, 1, 4]))
+        _log(f"random case {case}: M={M} d={d} pad={pad} g={g_dt} x={x_dt} beta={beta} wd={wd} "
+             f"flip={'yes' if flip else 'no'} x_off={x_off} momentum={momentum}")
+        assert _step_case(sv, M, d, g_dt, x_dt, beta, wd, steps=2, pad=pad, flip=flip, momentum=momentum,
+                          x_off=x_off) == 0
+
+
+def test_vote_randomised_shapes(sv):
+    rng = np.random.default_rng(77)
+    for case in range(40):
+        M = int(rng.integers(1, 300))
+        d = int(rng.integers(1, 40000))
+        extra = int(rng.integers(0, 4))
+        W = sv.words_for(d)
+        _log(f"random vote case {case}: M={M} d={d} stride={W + extra}")
+        rows = wl.random_words((M, W + extra), seed=1000 + case, device=DEV)[:, :W]
+        x = wl.gaussian((d + 3,), 0.02, seed=case, device=DEV)[int(rng.integers(0, 2)):][:d]
+        x_h = wl.to_numpy(x.contiguous()).copy()
+        vote_buf = torch.full((W + 2,), -1, dtype=torch.int64, device=DEV)
+        sv.majority_vote(rows, d, vote_buf[:W])
+        vote2 = torch.full((W,), -1, dtype=torch.int64, device=DEV)
+        sv.vote_apply(rows, d, x, 1e-3, 0.0, vote_out=vote2)
+        torch.cuda.synchronize()
+        ref = ora.vote_apply(_np_rows(rows), d, x_h, 1e-3, 0.0)
+        assert np.array_equal(wl.to_numpy(vote_buf[:W]), ref) and np.array_equal(wl.to_numpy(vote2), ref)
+        assert (vote_buf[W:] == -1).all()
+        assert np.array_equal(wl.to_numpy(x.contiguous()), x_h)
