@@ -212,6 +212,9 @@ def _step_case(sv, M, d, g_dtype, x_dtype, beta, wd, steps, pad=0, flip=None, mo
         v_ref = np.zeros((M, d), np.float32)
     W = sv.words_for(d)
     near_zero = 0
+    # a twin state stepped through the form without optional outputs (a separate kernel instantiation)
+    x_lean = x.clone()
+    v_lean = None if v is None else v.clone()
     for step in range(steps):
         g = wl.worker_gradients(mu, M, step, base_seed=500, noise_std=noise, dtype=g_dtype, row_stride=d + pad)
         vote_buf = torch.full((W + 2,), -1, dtype=torch.int64, device=DEV)
@@ -247,6 +250,11 @@ def _step_case(sv, M, d, g_dtype, x_dtype, beta, wd, steps, pad=0, flip=None, mo
         assert np.array_equal(wl.to_numpy(vote), vote_ref)
         x_gpu = wl.to_numpy(x.contiguous())
         assert np.array_equal(x_gpu, x_ref)
+        if flip is None:
+            sv.signum_step(g, v_lean, beta, x_lean, lr, wd)
+            torch.cuda.synchronize()
+            assert torch.equal(x_lean, x), "form without optional outputs disagrees (weights)"
+            assert v is None or torch.equal(v_lean, v), "form without optional outputs disagrees (momentum)"
     ref_buf = wl.gaussian((d + 8,), 0.02, seed=12, device=DEV).to(x_dtype)
     assert torch.equal(xbuf[:x_off], ref_buf[:x_off]) and torch.equal(xbuf[x_off + d:], ref_buf[x_off + d:])
     return near_zero
