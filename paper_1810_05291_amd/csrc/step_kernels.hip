@@ -21,10 +21,6 @@
 // the U*SUB momentum stores back to back: a read phase and a write burst per group.
 #include "device_utils.h"
 
-#ifndef SSV_SERIAL_READONLY
-#define SSV_SERIAL_READONLY 0
-#endif
-
 namespace ssv {
 
 template <typename GT, int VEC, int SUB, bool MOM, bool OUT, bool GUARD, int U>
@@ -33,7 +29,7 @@ __device__ __forceinline__ void worker_group(const StepArgs& a, int m0, int64_t 
     constexpr int64_t kTile = (int64_t)kWave * VEC * kWavesPerBlock;   // a wave's tiles are a block-row apart
     // one row load in flight per wave where momentum is written back (read/write mix); the
     // read-only forms (sign_pack, signSGD step) keep all loads of the group in flight
-    constexpr bool SERIAL = (VEC > 1) && (MOM || SSV_SERIAL_READONLY);
+    constexpr bool SERIAL = (VEC > 1) && MOM;
     float gv[U][SUB][VEC];
     float vv[U][SUB][VEC];
     const GT* __restrict__ g = static_cast<const GT*>(a.g);

@@ -20,13 +20,6 @@
 // per coordinate at fp32 and is dominated by the weights.
 #include "device_utils.h"
 
-#ifndef SSV_APPLY_UA
-#define SSV_APPLY_UA 4
-#endif
-#ifndef SSV_APPLY_SERIAL
-#define SSV_APPLY_SERIAL 0
-#endif
-
 namespace ssv {
 
 // Packed rows are read once: streaming loads.  Unlike the fused gradient step, this pure-read
@@ -193,7 +186,8 @@ __global__ __launch_bounds__(kBlock) void vote_apply_kernel(VoteArgs a) {
     XT* __restrict__ x = static_cast<XT*>(a.x);
     const int64_t cbase = tile * (int64_t)kTileCoords;
     constexpr int kIter = 32 / XV;                 // accesses per thread to cover the tile
-    constexpr int UA = (kIter % SSV_APPLY_UA == 0) ? SSV_APPLY_UA : 1;
+    constexpr int UA = 4;                          // independent weight accesses in flight per thread (1..8 measure alike)
+    static_assert(kIter % UA == 0, "the tile must split into groups of UA accesses");
     for (int i0 = 0; i0 < kIter; i0 += UA) {
         float xv[UA][XV];
         int n[UA];
@@ -205,9 +199,6 @@ __global__ __launch_bounds__(kBlock) void vote_apply_kernel(VoteArgs a) {
             n[u] = left_c >= XV ? XV : (left_c > 0 ? (int)left_c : 0);
             bits[u] = stage[off >> 5] >> (off & 31);
             if (n[u] > 0) load_vals_guarded<XT, XV>(x + cbase + off, n[u], xv[u]);
-#if SSV_APPLY_SERIAL
-            drain_memory_ops();
-#endif
         }
 #pragma unroll
         for (int u = 0; u < UA; ++u) {
