@@ -135,7 +135,12 @@ def test_config3_adversaries_unfused_pipeline(sv):
         xf = x0.clone()
         sv.vote_apply(tampered, d, xf, lr)
         torch.cuda.synchronize()
-        t_h = _host(tampered)
+        # the oracle tampers with its OWN packed signs: nothing it consumes comes from the GPU path
+        t_h = signs_ref.copy()
+        if mode == "invert":
+            t_h[:A] = ~t_h[:A]
+        else:
+            t_h[:A] = _host(wl.random_words((A, W), seed=77, device=DEV))
         vote_ref = ora.majority_vote(t_h, d)
         assert np.array_equal(_host(vote), vote_ref)
         x_ref = _host(x0).copy()
