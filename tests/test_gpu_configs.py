@@ -306,5 +306,5 @@ def test_more_than_2_pow_31_coordinates(sv):
     assert (_host(signs[:, W - 1:]) >> np.uint64(last_bits) == 0).all()
     tail0 = 64 * (W - 1)
     vote_tail, _ = ora.signum_step(_host(g[:, tail0:]), np.zeros((M, d - tail0), np.float32), beta,
-                                   _host(x[tail0:]).copy() * 0, lr)
+                                   np.zeros(d - tail0, np.uint16), lr)
     assert int(_host(vote[W - 1:])[0]) == int(vote_tail[0])

@@ -97,7 +97,8 @@ def _quadratic_run(sv, M, adversaries, steps, mode, seed):
     for k in range(steps):
         noise = wl.gaussian((M, d), 1.0, seed=seed + 1 + k, device=DEV)
         g = (x[None, :] + noise).contiguous()                       # gradient of the quadratic is x
-        g_h = _host(g)
+        # the oracle runs its own closed loop: its gradient comes from ITS weights plus the same noise
+        g_h = (x_ref[None, :] + _host(noise)).astype(np.float32)
         if mode == "invert":
             sv.signum_step(g, None, 0.0, x, lr, worker_flip=flip)
             ora.signum_step(g_h, None, 0.0, x_ref, lr, worker_flip=flip)
@@ -180,7 +181,9 @@ def test_launch_shape_knobs_keep_parity(env):
 
 def test_small_model_trains_through_the_flat_layout(sv):
     # a two-layer network on synthetic regression data, 5 simulated workers with their own mini-batches;
-    # many parameter tensors, one flat vector, one launch per step; trajectory followed by the oracle
+    # many parameter tensors, one flat vector, one launch per step.  The gradients (torch autograd) are the
+    # recorded inputs of each step; the oracle is fed the same recorded gradients and must land on the same
+    # weights and momenta.
     torch.manual_seed(0)
     M, steps = 5, 60
     shapes = [(64, 20), (64,), (1, 64), (1,)]
