@@ -90,20 +90,12 @@ __device__ __forceinline__ void apply_piece(XT* __restrict__ xp, int n, uint32_t
     store_vals_guarded<XT, XV>(xp, n, xv);
 }
 
-template <int PW, int NPL>
-__global__ __launch_bounds__(kBlock) void vote_kernel(VoteArgs a, int64_t nblocks, int remap) {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
-    const int64_t lb = logical_block(blockIdx.x, nblocks, remap);
-    if (lb >= nblocks) return;
-    const int64_t tile = lb * kWavesPerBlock + wave;
-    if (tile >= a.ntiles) return;
-    const int64_t ndw = 2 * a.W;
+// FULL = every lane of the wave has all its PW dwords inside the row (no per-lane bounds checks).
+template <int PW, int NPL, bool FULL>
+__device__ __forceinline__ void vote_tile(const VoteArgs& a, int64_t dw0, int nv) {
     const int64_t row_dw = 2 * a.stride_words;
-    const int64_t dw0 = (tile * kWave + lane) * PW;
-    const int64_t left = ndw - dw0;
-    const int nv = left >= PW ? PW : (left > 0 ? (int)left : 0);
     const uint32_t* __restrict__ p = reinterpret_cast<const uint32_t*>(a.signs) + dw0;
+    constexpr int kFullNv = PW;
 
     uint32_t pl[NPL][PW];
 #pragma unroll
@@ -115,21 +107,21 @@ __global__ __launch_bounds__(kBlock) void vote_kernel(VoteArgs a, int64_t nblock
     // the current one; the compiler is free to issue them early (loads only, nothing aliases).
     uint32_t cur[8][PW];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) load_slices<PW>(p + (int64_t)i * row_dw, (i < a.M) ? nv : 0, cur[i]);
+    for (int i = 0; i < 8; ++i) load_slices<PW>(p + (int64_t)i * row_dw, (i < a.M) ? (FULL ? kFullNv : nv) : 0, cur[i]);
     for (int r0 = 0; r0 < a.M; r0 += 8) {
         uint32_t nxt[8][PW];
         const int rn = r0 + 8;
         add_eight_rows<PW, NPL>(pl, cur);
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-            load_slices<PW>(p + (int64_t)(rn + i) * row_dw, (rn + i < a.M) ? nv : 0, nxt[i]);
+            load_slices<PW>(p + (int64_t)(rn + i) * row_dw, (rn + i < a.M) ? (FULL ? kFullNv : nv) : 0, nxt[i]);
 #pragma unroll
         for (int i = 0; i < 8; ++i)
 #pragma unroll
             for (int q = 0; q < PW; ++q) cur[i][q] = nxt[i][q];
     }
 
-    if (nv > 0) {
+    if (FULL || nv > 0) {
         uint32_t vt[PW];
 #pragma unroll
         for (int q = 0; q < PW; ++q) {
@@ -139,7 +131,7 @@ __global__ __launch_bounds__(kBlock) void vote_kernel(VoteArgs a, int64_t nblock
         }
         uint32_t* o = reinterpret_cast<uint32_t*>(a.vote_out) + dw0;
         if constexpr (PW == 4) {
-            if (nv == 4) {
+            if (FULL || nv == 4) {
                 u32x4 w = {vt[0], vt[1], vt[2], vt[3]};
                 *reinterpret_cast<u32x4*>(o) = w;
             } else {
@@ -150,6 +142,24 @@ __global__ __launch_bounds__(kBlock) void vote_kernel(VoteArgs a, int64_t nblock
             u32x2 w = {vt[0], vt[1]};
             *reinterpret_cast<u32x2*>(o) = w;
         }
+    }
+}
+
+template <int PW, int NPL>
+__global__ __launch_bounds__(kBlock) void vote_kernel(VoteArgs a, int64_t nblocks, int remap) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int64_t lb = logical_block(blockIdx.x, nblocks, remap);
+    if (lb >= nblocks) return;
+    const int64_t tile = lb * kWavesPerBlock + wave;
+    if (tile >= a.ntiles) return;
+    const int64_t ndw = 2 * a.W;
+    const int64_t dw0 = (tile * kWave + lane) * PW;
+    if ((tile + 1) * (int64_t)(kWave * PW) <= ndw) {          // wave-uniform: the whole tile is inside the row
+        vote_tile<PW, NPL, true>(a, dw0, PW);
+    } else {
+        const int64_t left = ndw - dw0;
+        vote_tile<PW, NPL, false>(a, dw0, left >= PW ? PW : (left > 0 ? (int)left : 0));
     }
 }
 
