@@ -33,7 +33,7 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--other-kernels", action="store_true",
                     help="also time the packed vote (d = 2^30, M = 255), the fused vote+apply (resnet50 size) and "
-                         "the bf16 fused step (M = 31, chunk of 2^26) and add them to the JSON line")
+                         "the large bf16 fused step (d = 1.5e9, M = 31, 23 chunk launches) and add them to the JSON line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="instead of the benchmark, run a plain 1 GiB device-to-device copy three times "
                          "(known traffic: 1 GiB read + 1 GiB written per copy) to scale rocprofv3's "
@@ -100,18 +100,30 @@ def other_kernels(torch, sv, wl, dev):
     out["vote_apply_resnet50_M15"] = {"ms": ms, "GB/s": b / ms / 1e6, "frac": b / ms / 1e6 / HBM_PEAK_GBS,
                                       "algorithmic_bytes": b, "note": "8 rotating buffer sets"}
     del sets
-    # bf16 fused step, M = 31, one chunk of 2^26 coordinates out of a 2^28-coordinate momentum (row stride 2^28)
-    M, chunk, nch = 31, 1 << 26, 4
-    dd = chunk * nch
-    v = torch.zeros((M, dd), device=dev)
-    x = wl.gaussian((dd,), 0.02, seed=3, device=dev).to(torch.bfloat16)
-    mu = wl.shared_mean(chunk, seed=4, device=dev)
-    g = wl.worker_gradients(mu, M, 0, base_seed=7, dtype=torch.bfloat16)
-    ms = time_launches(torch, lambda i: sv.signum_step(g, v[:, (i % nch) * chunk:(i % nch + 1) * chunk], 0.9,
-                                                       x[(i % nch) * chunk:(i % nch + 1) * chunk], 1e-5), 12, warmup=4)
-    b = (10 * M + 4) * chunk
-    out["signum_step_bf16_M31_chunk2^26"] = {"ms": ms, "GB/s": b / ms / 1e6, "frac": b / ms / 1e6 / HBM_PEAK_GBS,
-                                             "algorithmic_bytes": b}
+    # large bf16 fused step: d = 1.5e9, M = 31, fp32 momentum resident (186 GB), streamed in chunks of 2^26
+    # coordinates (one launch per chunk, gradients double-buffered); one step = 23 launches
+    M, d, chunk = 31, 1_500_000_000, 1 << 26
+    free, _ = torch.cuda.mem_get_info()
+    if free > (M * d * 4 + d * 2 + 2 * M * chunk * 2 + (4 << 30)):
+        nch = (d + chunk - 1) // chunk
+        v = torch.zeros((M, d), dtype=torch.float32, device=dev)
+        x = wl.gaussian((chunk,), 0.02, seed=3, device=dev).to(torch.bfloat16).repeat(nch)[:d].contiguous()
+        mu = wl.shared_mean(chunk, seed=4, device=dev)
+        g = [wl.worker_gradients(mu, M, s, base_seed=7, dtype=torch.bfloat16) for s in range(2)]
+
+        def large_step(i):
+            for c in range(nch):
+                c0, c1 = c * chunk, min(d, (c + 1) * chunk)
+                sv.signum_step(g[c % 2][:, :c1 - c0], v[:, c0:c1], 0.9, x[c0:c1], 1e-5)
+
+        ms = time_launches(torch, large_step, 3, warmup=1)
+        b = (10 * M + 4) * d
+        out["signum_step_bf16_d1.5e9_M31"] = {"ms": ms, "launches": nch, "GB/s": b / ms / 1e6,
+                                              "frac": b / ms / 1e6 / HBM_PEAK_GBS,
+                                              "worker_coords_per_s": M * d / ms * 1e3, "algorithmic_bytes": b}
+        del v, x, g
+    else:
+        out["signum_step_bf16_d1.5e9_M31"] = {"skipped": "not enough free HBM for the 186 GB momentum"}
     return out
 
 
