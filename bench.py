@@ -2,13 +2,16 @@
 
 A step is one pass of the whole hot path -- momentum, sign, majority vote, parameter update -- for
 all M simulated workers: one call of ssv_signum_step on gradients that are already resident in HBM.
-Prints ONE JSON line.
+Prints ONE JSON line.  Besides the headline it carries, under "other_kernels", the figures of every
+other entry point of the library at its own workload (each: milliseconds per launch, algorithmic
+bytes, GB/s, fraction of the 8 TB/s HBM peak), measured in the same process.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-other-kernels] [--no-cpu-baseline]
 """
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -17,7 +20,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
-BYTES_PER_COORD = 15 * 12 + 8  # per coordinate: M x (read g, read v, write v) fp32 + read/write x fp32
+RESNET50_D = 25_557_032
 
 
 def parse_args():
@@ -26,14 +29,18 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workers", type=int, default=15)
-    ap.add_argument("--d", type=int, default=25_557_032)
+    ap.add_argument("--d", type=int, default=RESNET50_D)
     ap.add_argument("--row-align", type=int, default=32,
-                    help="round row strides up to a multiple of this many elements")
+                    help="round row strides of the headline run up to a multiple of this many elements "
+                         "(32 fp32 = 128 bytes; 1 = the natural [M][d] layout)")
     ap.add_argument("--grad-sets", type=int, default=8, help="distinct pre-generated gradient sets that are cycled")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--other-kernels", action="store_true",
-                    help="also time the packed vote (d = 2^30, M = 255), the fused vote+apply (resnet50 size) and "
-                         "the large bf16 fused step (d = 1.5e9, M = 31, 23 chunk launches) and add them to the JSON line")
+    ap.add_argument("--no-other-kernels", action="store_true",
+                    help="skip the secondary measurements (copy yardstick, unfused entry points, natural-stride run, "
+                         "packed vote at d = 2^30 / M = 255, bf16 step at d = 1.5e9 / M = 31)")
+    ap.add_argument("--other-kernels", action="store_true", help="accepted for compatibility: they run by default")
+    ap.add_argument("--quick", action="store_true",
+                    help="a tenth of the launches per secondary measurement (for counter-collection runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="instead of the benchmark, run a plain 1 GiB device-to-device copy three times "
                          "(known traffic: 1 GiB read + 1 GiB written per copy) to scale rocprofv3's "
@@ -43,7 +50,7 @@ def parse_args():
 
 
 def read_traffic(name):
-    """Measured HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this kernel and workload, if there is one."""
     path = os.path.join(ROOT, "profiles", name)
     try:
         with open(path) as f:
@@ -56,7 +63,7 @@ def read_traffic(name):
 
 
 def time_launches(torch, fn, iters, warmup=2):
-    """Average milliseconds per call of fn() over `iters` back-to-back launches (events on the current stream)."""
+    """Average milliseconds per call of fn(i) over `iters` back-to-back launches (events on the current stream)."""
     for i in range(warmup):
         fn(i)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -69,61 +76,112 @@ def time_launches(torch, fn, iters, warmup=2):
     return e0.elapsed_time(e1) / iters
 
 
-def other_kernels(torch, sv, wl, dev):
-    """Secondary measurements: the kernels that are not the headline, at their own workloads."""
+def entry(ms, nbytes, **extra):
+    out = {"ms": ms, "algorithmic_bytes": nbytes, "GB/s": nbytes / ms / 1e6, "frac": nbytes / ms / 1e6 / HBM_PEAK_GBS}
+    out.update(extra)
+    return out
+
+
+def other_kernels(torch, sv, wl, dev, quick):
+    """Secondary measurements: every entry point that is not the headline, at its own workload.  Working sets are
+    rotated over several buffer sets wherever one set would fit the 256 MB Infinity Cache."""
     out = {}
-    # yardstick: the library's plain streaming copy (1:1 read/write), 1.5 GB like one gradient set
-    src = wl.gaussian((15 * 25_557_056,), 1.0, seed=1, device=dev)
+    scale = 0.1 if quick else 1.0
+
+    def n(iters):
+        return max(2, int(iters * scale))
+
+    M, d = 15, RESNET50_D
+    W = sv.words_for(d)
+    stride = ((d + 31) // 32) * 32                       # rows on 128-byte boundaries
+    strideW = ((W + 15) // 16) * 16
+
+    # ---- yardstick: the library's plain streaming copy (1:1 read/write), 1.5 GB like one gradient set
+    src = wl.gaussian((M * stride,), 1.0, seed=1, device=dev)
     dst = torch.empty_like(src)
-    ms = time_launches(torch, lambda i: sv.bench_copy(src, dst), 20)
-    b = 2.0 * src.numel() * 4
-    out["stream_copy_1.5GB"] = {"ms": ms, "GB/s": b / ms / 1e6, "frac": b / ms / 1e6 / HBM_PEAK_GBS,
-                                "note": "plain 16-byte non-temporal copy, bytes read + written"}
+    ms = time_launches(torch, lambda i: sv.bench_copy(src, dst), n(20))
+    out["stream_copy_1.5GB"] = entry(ms, 2.0 * src.numel() * 4, note="plain 16-byte non-temporal copy, bytes read + written")
     del src, dst
-    # packed majority vote, d = 2^30, M = 255 (uniform random bits: the kernel is data-oblivious)
-    M, d = 255, 1 << 30
-    W = sv.words_for(d)
-    rows = wl.random_words((M, W), seed=5, device=dev)
+
+    # ---- worker-side entry points on the resnet50-sized gradients (4 rotating gradient sets = 6 GB)
+    mu = wl.shared_mean(d, seed=1, device=dev)
+    grads = [wl.worker_gradients(mu, M, s, base_seed=2000, row_stride=stride) for s in range(4)]
+    signs = torch.empty((M, strideW), dtype=torch.int64, device=dev)[:, :W]
+    ms = time_launches(torch, lambda i: sv.sign_pack(grads[i % 4], signs), n(40))
+    out["sign_pack_resnet50_M15"] = entry(ms, (4 + 1 / 8) * M * d, bytes_per_worker_coordinate=4.125)
+    v = torch.zeros((M, stride), device=dev)[:, :d]
+    ms = time_launches(torch, lambda i: sv.signum_momentum_pack(grads[i % 4], v, 0.9, signs), n(40))
+    out["signum_momentum_pack_resnet50_M15"] = entry(ms, (12 + 1 / 8) * M * d, bytes_per_worker_coordinate=12.125)
+
+    # ---- unfused pipeline: momentum + pack, vote, update (three launches per step)
+    x = wl.gaussian((d,), 0.02, seed=2, device=dev)
     vote = torch.empty((W,), dtype=torch.int64, device=dev)
-    ms = time_launches(torch, lambda i: sv.majority_vote(rows, d, vote), 10)
-    b = (M + 1) / 8 * d
-    out["majority_vote_d2^30_M255"] = {"ms": ms, "GB/s": b / ms / 1e6, "frac": b / ms / 1e6 / HBM_PEAK_GBS,
-                                        "coords_per_s": d / ms * 1e3, "algorithmic_bytes": b}
+
+    def unfused(i):
+        sv.signum_momentum_pack(grads[i % 4], v, 0.9, signs)
+        sv.majority_vote(signs, d, vote)
+        sv.apply_sign_update(x, vote, 1e-4)
+
+    ms = time_launches(torch, unfused, n(40))
+    out["unfused_pipeline_resnet50_M15"] = entry(ms, (12.125 * M + (M + 1) / 8 + 8.125) * d, launches=3)
+
+    # ---- the headline kernel on the natural [M][d] layout (row stride d: rows only 32-byte phased)
+    gnat = [wl.worker_gradients(mu, M, s, base_seed=3000, row_stride=d) for s in range(4)]
+    vnat = torch.zeros((M, d), device=dev)
+    ms = time_launches(torch, lambda i: sv.signum_step(gnat[i % 4], vnat, 0.9, x, 1e-4), n(50), warmup=3)
+    out["signum_step_resnet50_M15_natural_stride"] = entry(ms, (12.0 * M + 8) * d, row_stride=d,
+                                                           worker_coords_per_s=M * d / ms * 1e3)
+    del gnat, vnat, grads, v, mu
+
+    # ---- server-side and update entry points, 8 rotating buffer sets (packed rows 8 x 48 MB, weights 8 x 102 MB)
+    xs = [wl.gaussian((d,), 0.02, seed=20 + k, device=dev) for k in range(8)]
+    votes = [wl.random_words((W,), seed=30 + k, device=dev) for k in range(8)]
+    ms = time_launches(torch, lambda i: sv.apply_sign_update(xs[i % 8], votes[i % 8], 1e-4), n(80), warmup=8)
+    out["apply_sign_update_resnet50"] = entry(ms, (8 + 1 / 8) * d, note="8 rotating buffer sets")
+    for name, sw in (("vote_apply_resnet50_M15", strideW), ("vote_apply_resnet50_M15_natural_stride", W)):
+        rows = [wl.random_words((M, sw), seed=10 + k, device=dev)[:, :W] for k in range(8)]
+        ms = time_launches(torch, lambda i: sv.vote_apply(rows[i % 8], d, xs[i % 8], 1e-4), n(80), warmup=8)
+        out[name] = entry(ms, (M / 8 + 8) * d, row_stride_words=sw, note="8 rotating buffer sets")
+        if sw == strideW:
+            ms = time_launches(torch, lambda i: sv.majority_vote(rows[i % 8], d, votes[i % 8]), n(80), warmup=8)
+            out["majority_vote_resnet50_M15"] = entry(ms, (M + 1) / 8 * d, note="8 rotating buffer sets")
+        del rows
+    del xs, votes, x, vote, signs
+    torch.cuda.empty_cache()
+
+    # ---- packed majority vote, d = 2^30, M = 255 (uniform random bits: the kernel is data-oblivious)
+    Mv, dv = 255, 1 << 30
+    Wv = sv.words_for(dv)
+    rows = wl.random_words((Mv, Wv), seed=5, device=dev)
+    vote = torch.empty((Wv,), dtype=torch.int64, device=dev)
+    ms = time_launches(torch, lambda i: sv.majority_vote(rows, dv, vote), n(10))
+    out["majority_vote_d2^30_M255"] = entry(ms, (Mv + 1) / 8 * dv, coords_per_s=dv / ms * 1e3)
     del rows, vote
-    # fused vote + apply at the resnet50 size, 8 rotating buffer sets (2 GB, beyond the 256 MB Infinity Cache)
-    M, d = 15, 25_557_032
-    W = sv.words_for(d)
-    sets = [(wl.random_words((M, W), seed=10 + k, device=dev), wl.gaussian((d,), 0.02, seed=20 + k, device=dev))
-            for k in range(8)]
-    ms = time_launches(torch, lambda i: sv.vote_apply(sets[i % 8][0], d, sets[i % 8][1], 1e-4), 80, warmup=8)
-    b = (M / 8 + 8) * d
-    out["vote_apply_resnet50_M15"] = {"ms": ms, "GB/s": b / ms / 1e6, "frac": b / ms / 1e6 / HBM_PEAK_GBS,
-                                      "algorithmic_bytes": b, "note": "8 rotating buffer sets"}
-    del sets
-    # large bf16 fused step: d = 1.5e9, M = 31, fp32 momentum resident (186 GB), streamed in chunks of 2^26
+    torch.cuda.empty_cache()
+
+    # ---- large bf16 fused step: d = 1.5e9, M = 31, fp32 momentum resident (186 GB), streamed in chunks of 2^26
     # coordinates (one launch per chunk, gradients double-buffered); one step = 23 launches
-    M, d, chunk = 31, 1_500_000_000, 1 << 26
+    Ml, dl, chunk = 31, 1_500_000_000, 1 << 26
     free, _ = torch.cuda.mem_get_info()
-    if free > (M * d * 4 + d * 2 + 2 * M * chunk * 2 + (4 << 30)):
-        nch = (d + chunk - 1) // chunk
-        v = torch.zeros((M, d), dtype=torch.float32, device=dev)
-        x = wl.gaussian((chunk,), 0.02, seed=3, device=dev).to(torch.bfloat16).repeat(nch)[:d].contiguous()
+    if free > (Ml * dl * 4 + dl * 2 + 2 * Ml * chunk * 2 + (4 << 30)):
+        nch = (dl + chunk - 1) // chunk
+        v = torch.zeros((Ml, dl), dtype=torch.float32, device=dev)
+        x = wl.gaussian((chunk,), 0.02, seed=3, device=dev).to(torch.bfloat16).repeat(nch)[:dl].contiguous()
         mu = wl.shared_mean(chunk, seed=4, device=dev)
-        g = [wl.worker_gradients(mu, M, s, base_seed=7, dtype=torch.bfloat16) for s in range(2)]
+        g = [wl.worker_gradients(mu, Ml, s, base_seed=7, dtype=torch.bfloat16) for s in range(2)]
 
         def large_step(i):
             for c in range(nch):
-                c0, c1 = c * chunk, min(d, (c + 1) * chunk)
+                c0, c1 = c * chunk, min(dl, (c + 1) * chunk)
                 sv.signum_step(g[c % 2][:, :c1 - c0], v[:, c0:c1], 0.9, x[c0:c1], 1e-5)
 
-        ms = time_launches(torch, large_step, 3, warmup=1)
-        b = (10 * M + 4) * d
-        out["signum_step_bf16_d1.5e9_M31"] = {"ms": ms, "launches": nch, "GB/s": b / ms / 1e6,
-                                              "frac": b / ms / 1e6 / HBM_PEAK_GBS,
-                                              "worker_coords_per_s": M * d / ms * 1e3, "algorithmic_bytes": b}
-        del v, x, g
+        ms = time_launches(torch, large_step, max(2, n(3)), warmup=1)
+        out["signum_step_bf16_d1.5e9_M31"] = entry(ms, (10.0 * Ml + 4) * dl, launches=nch,
+                                                   worker_coords_per_s=Ml * dl / ms * 1e3)
+        del v, x, g, mu
     else:
         out["signum_step_bf16_d1.5e9_M31"] = {"skipped": "not enough free HBM for the 186 GB momentum"}
+    torch.cuda.empty_cache()
     return out
 
 
@@ -197,10 +255,16 @@ def main():
         sv.signum_step(grads[s % nsets], v, beta, x, lr)
     torch.cuda.synchronize()
     parity = None
+    mismatched = near_zero = sign_exceptions = None
     if x_ref is not None and Wm <= nsets:
-        ok = np.array_equal(wl.to_numpy(x[:ds]), x_ref) and \
-            np.array_equal(wl.to_numpy(v[:, :ds].contiguous()), v_ref)
-        parity = "bit-exact vs oracle on the sample after warmup" if ok else "MISMATCH vs oracle"
+        x_gpu, v_gpu = wl.to_numpy(x[:ds]), wl.to_numpy(v[:, :ds].contiguous())
+        # elements of the weights and momenta of the sample whose bits differ from the oracle's
+        mismatched = int((x_gpu.view(np.uint32) != x_ref.view(np.uint32)).sum()
+                         + (v_gpu.view(np.uint32) != v_ref.view(np.uint32)).sum())
+        tiny = np.abs(v_ref) < 1e-6 * np.abs(v_ref).max()
+        near_zero = int(tiny.sum())
+        sign_exceptions = int(((v_gpu >= 0) != (v_ref >= 0)).sum())
+        parity = "bit-exact vs oracle on the sample after warmup" if mismatched == 0 else "MISMATCH vs oracle"
 
     # ---- timed region: exactly K steps ---------------------------------------------------------------
     ev0 = torch.cuda.Event(enable_timing=True)
@@ -216,13 +280,26 @@ def main():
     wall_ms = (t1 - t0) * 1e3 / K
     kern_ms = ev0.elapsed_time(ev1) / K
 
+    # ---- a second pass of K steps with an event after every launch: the median launch ---------------
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+    evs[0].record()
+    for s in range(K):
+        sv.signum_step(grads[(Wm + s) % nsets], v, beta, x, lr)
+        evs[s + 1].record()
+    torch.cuda.synchronize()
+    per_launch = [evs[s].elapsed_time(evs[s + 1]) for s in range(K)]
+    median_ms = statistics.median(per_launch)
+
     algo_bytes = float(M * 12 + 8) * d
     achieved = algo_bytes / (kern_ms * 1e-3) / 1e9
+    default_workload = (M == 15 and d == RESNET50_D and stride % 32 == 0)
+    traffic = read_traffic("signum_step_resnet50_pmc.txt") if default_workload else None
     out = {
         "metric": "voted coords/sec (M*d/s), fused Signum step (momentum + sign + majority vote + update)",
         "value": M * d / (wall_ms * 1e-3),
         "unit": "worker-coordinates/s (M*d/s)",
         "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": wall_ms,
+        "median_ms_per_step": median_ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "resnet50-sized fused Signum step", "d": d, "M": M, "beta": beta, "lr": lr,
@@ -230,15 +307,25 @@ def main():
                    "gradient_sets_cycled": nsets, "kernel": "ssv_signum_step"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": read_traffic("signum_step_resnet50_pmc.txt"),
+                     "traffic": traffic,
+                     "traffic_source": ("profiles/signum_step_resnet50_pmc.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of "
+                                        "this kernel on this workload, scaled by a copy of known size; a committed "
+                                        "measurement, not taken in this run") if traffic else None,
                      "kernel_ms": kern_ms, "algorithmic_bytes_per_launch": algo_bytes},
+        "bytes_per_voted_coordinate": {"algorithmic": algo_bytes / d,
+                                       "measured_hbm": (traffic / d) if traffic else None},
         "cpu_baseline": cpu,
         "parity": parity,
+        "mismatched_elements": mismatched,
+        "near_zero_momentum_entries": near_zero,
+        "near_zero_sign_exceptions": sign_exceptions,
     }
-    if args.other_kernels:
+    if not args.no_other_kernels:
         del grads, v, x, mu
         torch.cuda.empty_cache()
-        out["other_kernels"] = other_kernels(torch, sv, wl, dev)
+        others = other_kernels(torch, sv, wl, dev, args.quick)
+        out["other_kernels"] = others
+        out["copy_ceiling_GBs"] = others["stream_copy_1.5GB"]["GB/s"]
     print(json.dumps(out), flush=True)
     if parity is not None and parity.startswith("MISMATCH"):
         sys.exit(1)

@@ -20,8 +20,13 @@
  *     bf16 values are widened to fp32 (exact), results rounded to nearest even.
  *
  * Memory and ownership: every pointer is DEVICE memory owned by the caller unless the argument
- * is documented as host memory.  The library allocates nothing, keeps no state between calls and
- * never frees.  Matrices are row-major, one row per worker, with the row stride given in
+ * is documented as host memory.  The library allocates nothing, never frees, and keeps no state
+ * between calls apart from one measurement switch read from the environment on first use:
+ *     SSV_TUNE_STEP_SERIAL=0   let the momentum forms of the fused step (ssv_signum_step with v,
+ *                              ssv_signum_momentum_pack) keep all row loads of a worker group in
+ *                              flight instead of one load per wavefront at a time.  Results are
+ *                              identical; on MI355X it is about 10% slower.  It exists so that the
+ *                              two schedules can be profiled against each other; leave it unset.  Matrices are row-major, one row per worker, with the row stride given in
  * elements (or in 64-bit words for packed rows).  Inputs must not overlap outputs.  v and x are
  * updated in place.
  *

@@ -113,6 +113,41 @@ def _ptr(t):
     return None if t is None else t.data_ptr()
 
 
+def _packed_rows(t, M, d, name):
+    """Row stride (words) of a packed [M][>= ceil(d/64)] int64 tensor, after checking that it can hold M rows of d bits."""
+    if t.dtype != torch.int64:
+        raise ValueError(f"{name} must be torch.int64 (bit patterns of the packed words)")
+    rows, cols, stride = _rows(t)
+    if rows != M:
+        raise ValueError(f"{name} has {rows} rows, expected {M}")
+    if cols < words_for(d):
+        raise ValueError(f"{name} rows hold {cols} words, {words_for(d)} needed for d = {d}")
+    return stride
+
+
+def _packed_vec(t, d, name):
+    """A contiguous int64 vector of at least ceil(d/64) words."""
+    if t.dtype != torch.int64:
+        raise ValueError(f"{name} must be torch.int64 (bit patterns of the packed words)")
+    if _vec(t).numel() < words_for(d):
+        raise ValueError(f"{name} holds {t.numel()} words, {words_for(d)} needed for d = {d}")
+    return t
+
+
+def _weights(x, d):
+    _dt(x)
+    if _vec(x).numel() != d:
+        raise ValueError(f"x has {x.numel()} elements, expected d = {d}")
+    return x
+
+
+def _dim(d):
+    d = int(d)
+    if d < 1:
+        raise ValueError("d must be positive")
+    return d
+
+
 def _stream(dev):
     return torch.cuda.current_stream(dev).cuda_stream
 
@@ -125,10 +160,11 @@ def _check(name, rc):
 def sign_pack(x, signs=None):
     """signs[m] = packed (x[m] >= 0) for every row of the 2-D tensor x."""
     M, d, xs = _rows(x)
+    ss = None if signs is None else _packed_rows(signs, M, d, "signs")
     dev = _dev(x, signs)
     if signs is None:
         signs = torch.empty((M, words_for(d)), dtype=torch.int64, device=dev)
-    _, _, ss = _rows(signs)
+        ss = words_for(d)
     _check("ssv_sign_pack", load_library().ssv_sign_pack(_ptr(x), _dt(x), M, d, xs, _ptr(signs), ss, _stream(dev)))
     return signs
 
@@ -139,10 +175,11 @@ def signum_momentum_pack(g, v, beta, signs=None):
     Mv, dv, vs = _rows(v)
     if (Mv, dv) != (M, d) or v.dtype != torch.float32:
         raise ValueError("v must be fp32 with the shape of g")
+    ss = None if signs is None else _packed_rows(signs, M, d, "signs")
     dev = _dev(g, v, signs)
     if signs is None:
         signs = torch.empty((M, words_for(d)), dtype=torch.int64, device=dev)
-    _, _, ss = _rows(signs)
+        ss = words_for(d)
     _check("ssv_signum_momentum_pack",
            load_library().ssv_signum_momentum_pack(_ptr(g), _dt(g), _ptr(v), M, d, gs, vs, float(beta), _ptr(signs),
                                                    ss, _stream(dev)))
@@ -151,29 +188,41 @@ def signum_momentum_pack(g, v, beta, signs=None):
 
 def majority_vote(signs, d, vote=None):
     """Packed element-wise majority over the rows of `signs` (ties -> +1)."""
-    M, _, ss = _rows(signs)
+    d = _dim(d)
+    M = signs.shape[0] if signs.dim() == 2 else 0
+    ss = _packed_rows(signs, M, d, "signs")
+    if vote is not None:
+        _packed_vec(vote, d, "vote")
     dev = _dev(signs, vote)
     if vote is None:
         vote = torch.empty((words_for(d),), dtype=torch.int64, device=dev)
-    _check("ssv_majority_vote", load_library().ssv_majority_vote(_ptr(signs), M, d, ss, _ptr(_vec(vote)), _stream(dev)))
+    _check("ssv_majority_vote", load_library().ssv_majority_vote(_ptr(signs), M, d, ss, _ptr(vote), _stream(dev)))
     return vote
 
 
 def apply_sign_update(x, vote, lr, weight_decay=0.0):
     """x <- x - lr (vote + weight_decay x) in place."""
+    d = _dim(x.numel())
+    _weights(x, d)
+    _packed_vec(vote, d, "vote")
     dev = _dev(x, vote)
     _check("ssv_apply_sign_update",
-           load_library().ssv_apply_sign_update(_ptr(_vec(x)), _dt(x), x.numel(), _ptr(_vec(vote)), float(lr),
-                                                float(weight_decay), _stream(dev)))
+           load_library().ssv_apply_sign_update(_ptr(x), _dt(x), d, _ptr(vote), float(lr), float(weight_decay),
+                                                _stream(dev)))
     return x
 
 
 def vote_apply(signs, d, x, lr, weight_decay=0.0, vote_out=None):
     """Fused majority vote + update from packed rows."""
-    M, _, ss = _rows(signs)
+    d = _dim(d)
+    M = signs.shape[0] if signs.dim() == 2 else 0
+    ss = _packed_rows(signs, M, d, "signs")
+    _weights(x, d)
+    if vote_out is not None:
+        _packed_vec(vote_out, d, "vote_out")
     dev = _dev(signs, x, vote_out)
     _check("ssv_vote_apply",
-           load_library().ssv_vote_apply(_ptr(signs), M, d, ss, _ptr(_vec(x)), _dt(x), float(lr), float(weight_decay),
+           load_library().ssv_vote_apply(_ptr(signs), M, d, ss, _ptr(x), _dt(x), float(lr), float(weight_decay),
                                          _ptr(vote_out), _stream(dev)))
     return x
 
@@ -186,15 +235,16 @@ def signum_step(g, v, beta, x, lr, weight_decay=0.0, vote_out=None, signs_out=No
         Mv, dv, vs = _rows(v)
         if (Mv, dv) != (M, d) or v.dtype != torch.float32:
             raise ValueError("v must be fp32 with the shape of g")
-    if _vec(x).numel() != d:
-        raise ValueError("x must have d elements")
-    dev = _dev(g, v, x, vote_out, signs_out)
-    ss = 0
-    if signs_out is not None:
-        _, _, ss = _rows(signs_out)
+    _weights(x, d)
+    if vote_out is not None:
+        _packed_vec(vote_out, d, "vote_out")
+    ss = 0 if signs_out is None else _packed_rows(signs_out, M, d, "signs_out")
     flip = None
     if worker_flip is not None:
+        if len(worker_flip) != M:
+            raise ValueError(f"worker_flip has {len(worker_flip)} entries, expected M = {M}")
         flip = (ctypes.c_uint8 * M)(*[1 if f else 0 for f in worker_flip])
+    dev = _dev(g, v, x, vote_out, signs_out)
     _check("ssv_signum_step",
            load_library().ssv_signum_step(_ptr(g), _dt(g), _ptr(v), M, d, gs, vs, float(beta), _ptr(x), _dt(x),
                                           float(lr), float(weight_decay), _ptr(vote_out), _ptr(signs_out), ss,

@@ -1,5 +1,6 @@
 // The C ABI of libsignvote (declared in include/signvote.h): argument validation, choice of the
-// load-width path from pointer/stride alignment, and kernel dispatch.  No allocation, no state.
+// load-width path from pointer/stride alignment, and kernel dispatch.  No allocation; the only state is
+// the measurement switch SSV_TUNE_STEP_SERIAL, read from the environment once per process.
 #include <cmath>
 #include <cstdlib>
 
@@ -8,13 +9,11 @@
 
 namespace ssv {
 
-static int env_int(const char* name) {
-    const char* s = std::getenv(name);
-    return s ? std::atoi(s) : 0;
-}
-
 const Tuning& tuning() {
-    static const Tuning t = {env_int("SSV_TUNE_STEP_SUB"), env_int("SSV_TUNE_XCD_REMAP")};
+    static const Tuning t = [] {
+        const char* s = std::getenv("SSV_TUNE_STEP_SERIAL");
+        return Tuning{(s != nullptr && s[0] == '0' && s[1] == '\0') ? 0 : 1};
+    }();
     return t;
 }
 

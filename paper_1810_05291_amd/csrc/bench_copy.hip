@@ -19,7 +19,8 @@ extern "C" int ssv_bench_copy(const void* src, void* dst, int64_t bytes, void* s
     if (reinterpret_cast<uintptr_t>(src) % 16 != 0 || reinterpret_cast<uintptr_t>(dst) % 16 != 0) return SSV_ERR_ALIGN;
     const int64_t n = bytes / 16;
     int64_t grid = (n + ssv::kBlock - 1) / ssv::kBlock;
-    if (grid > 0x40000000LL) grid = 0x40000000LL;
+    if (grid > 0x40000000LL) grid = 0x40000000LL;      // defensive: 2^30 blocks cover 4 TiB, beyond any buffer here
+    (void)hipGetLastError();                           // a stale error of an earlier call is not this launch's
     hipLaunchKernelGGL(ssv::copy_kernel, dim3((unsigned)grid), dim3(ssv::kBlock), 0, static_cast<hipStream_t>(stream),
                        static_cast<const ssv::f32x4*>(src), static_cast<ssv::f32x4*>(dst), n);
     return hipGetLastError() == hipSuccess ? SSV_OK : SSV_ERR_HIP;

@@ -68,10 +68,9 @@ hipError_t launch_step(const StepArgs& a, int g_dt, int x_dt, bool vector_ok, hi
 hipError_t launch_vote(const VoteArgs& a, int x_dt, bool rows16, bool x_vector_ok, hipStream_t s);
 hipError_t launch_apply(const ApplyArgs& a, int x_dt, bool x_vector_ok, hipStream_t s);
 
-// Launch-shape knobs, read once from the environment (SSV_TUNE_*); 0 / unset = built-in default.
+// Measurement switch, read once per process from the environment (documented in include/signvote.h).
 struct Tuning {
-    int step_sub;              // tiles a wave of the step kernel holds at once (1, 2 or 4)
-    int xcd_remap;             // 1 = give each XCD a contiguous range of tiles
+    int step_serial;           // 1 (default) = one row load in flight per wave in the momentum forms of the step kernel
 };
 const Tuning& tuning();
 

@@ -156,13 +156,4 @@ __device__ __forceinline__ void pack_store_tile(uint64_t* __restrict__ row, int6
     }
 }
 
-// Physical block id -> logical block id.  Workgroups are handed to the 8 XCDs round-robin; with
-// the remap on, XCD k walks the k-th contiguous eighth of the logical blocks, so neighbouring
-// tiles (which share cache lines when rows are not line-aligned) meet in one XCD's L2.
-__device__ __forceinline__ int64_t logical_block(int64_t phys, int64_t nblocks_logical, int remap) {
-    if (!remap) return phys;
-    int64_t chunk = (nblocks_logical + 7) / 8;
-    return (phys % 8) * chunk + phys / 8;
-}
-
 }  // namespace ssv

@@ -23,13 +23,12 @@
 
 namespace ssv {
 
-template <typename GT, int VEC, int SUB, bool MOM, bool OUT, bool GUARD, int U>
+template <typename GT, int VEC, int SUB, bool MOM, bool OUT, bool GUARD, bool SERIAL, int U>
 __device__ __forceinline__ void worker_group(const StepArgs& a, int m0, int64_t j0, const int (&nvalid)[SUB],
                                              int lane, int64_t tile0, uint32_t (&cnt)[SUB][VEC]) {
     constexpr int64_t kTile = (int64_t)kWave * VEC * kWavesPerBlock;   // a wave's tiles are a block-row apart
-    // one row load in flight per wave where momentum is written back (read/write mix); the
-    // read-only forms (sign_pack, signSGD step) keep all loads of the group in flight
-    constexpr bool SERIAL = (VEC > 1) && MOM;
+    // SERIAL: one row load in flight per wave.  Chosen by the launcher where momentum is written back
+    // (read/write mix); the read-only forms (sign_pack, signSGD step) keep all loads of the group in flight.
     float gv[U][SUB][VEC];
     float vv[U][SUB][VEC];
     const GT* __restrict__ g = static_cast<const GT*>(a.g);
@@ -95,7 +94,7 @@ __device__ __forceinline__ void worker_group(const StepArgs& a, int m0, int64_t 
 }
 
 // tile0 = index of the wave's first tile of 64*VEC coordinates; its s-th tile is tile0 + 4 s
-template <typename GT, typename XT, int VEC, int SUB, bool MOM, bool APPLY, bool OUT, bool GUARD>
+template <typename GT, typename XT, int VEC, int SUB, bool MOM, bool APPLY, bool OUT, bool GUARD, bool SERIAL>
 __device__ __forceinline__ void step_tiles(const StepArgs& a, int64_t tile0, int lane) {
     constexpr int64_t kTile = (int64_t)kWave * VEC * kWavesPerBlock;
     const int64_t j0 = tile0 * (int64_t)(kWave * VEC) + (int64_t)lane * VEC;
@@ -116,8 +115,9 @@ __device__ __forceinline__ void step_tiles(const StepArgs& a, int64_t tile0, int
 
     constexpr int U = 2;
     int m = 0;
-    for (; m + U <= a.M; m += U) worker_group<GT, VEC, SUB, MOM, OUT, GUARD, U>(a, m, j0, nvalid, lane, tile0, cnt);
-    if (m < a.M) worker_group<GT, VEC, SUB, MOM, OUT, GUARD, 1>(a, m, j0, nvalid, lane, tile0, cnt);
+    for (; m + U <= a.M; m += U)
+        worker_group<GT, VEC, SUB, MOM, OUT, GUARD, SERIAL, U>(a, m, j0, nvalid, lane, tile0, cnt);
+    if (m < a.M) worker_group<GT, VEC, SUB, MOM, OUT, GUARD, SERIAL, 1>(a, m, j0, nvalid, lane, tile0, cnt);
 
 #pragma unroll
     for (int s = 0; s < SUB; ++s) {
@@ -147,74 +147,76 @@ __device__ __forceinline__ void step_tiles(const StepArgs& a, int64_t tile0, int
 // touch four adjacent tiles, i.e. one contiguous 4 KiB run of every row.  The waves of the blocks
 // after them take the remaining (fewer than 4*SUB + 1) tiles one by one with bounds checks.
 // OUT = false is the lean form without optional outputs (packed signs, packed vote, flips).
-template <typename GT, typename XT, int VEC, int SUB, bool MOM, bool APPLY, bool OUT>
-__global__ __launch_bounds__(kBlock) void step_kernel(StepArgs a, int64_t nfull, int64_t nblocks, int remap) {
+template <typename GT, typename XT, int VEC, int SUB, bool MOM, bool APPLY, bool OUT, bool SERIAL>
+__global__ __launch_bounds__(kBlock) void step_kernel(StepArgs a, int64_t nfull) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
-    const int64_t lb = logical_block(blockIdx.x, nblocks, remap);
-    if (lb >= nblocks) return;
+    const int64_t lb = blockIdx.x;
     if (lb < nfull) {
-        step_tiles<GT, XT, VEC, SUB, MOM, APPLY, OUT, false>(a, lb * (kWavesPerBlock * SUB) + wave, lane);
+        step_tiles<GT, XT, VEC, SUB, MOM, APPLY, OUT, false, SERIAL>(a, lb * (kWavesPerBlock * SUB) + wave, lane);
     } else {
         const int64_t tile = nfull * (kWavesPerBlock * SUB) + (lb - nfull) * kWavesPerBlock + wave;
-        if (tile < a.ntiles) step_tiles<GT, XT, VEC, 1, MOM, APPLY, OUT, true>(a, tile, lane);
+        if (tile < a.ntiles) step_tiles<GT, XT, VEC, 1, MOM, APPLY, OUT, true, false>(a, tile, lane);
     }
 }
 
-template <typename GT, typename XT, int VEC, int SUB, bool MOM, bool APPLY, bool OUT>
+// Tiles a wave of the step kernel holds at once.  4 is the measured optimum on MI355X (1 and 2 cost
+// 3-8% on the resnet50-sized step).
+constexpr int kStepSub = 4;
+
+template <typename GT, typename XT, int VEC, bool MOM, bool APPLY, bool OUT, bool SERIAL>
 static hipError_t launch_out(StepArgs a, hipStream_t s) {
-    const Tuning& tn = tuning();
+    constexpr int SUB = kStepSub;
     constexpr int64_t kTile = (int64_t)kWave * VEC;
     constexpr int64_t kBlockTiles = (int64_t)kWavesPerBlock * SUB;
     a.ntiles = (a.d + kTile - 1) / kTile;
     const int64_t nfull = a.d / (kTile * kBlockTiles);
     const int64_t tail_tiles = a.ntiles - nfull * kBlockTiles;
-    const int64_t nblocks = nfull + (tail_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
-    const int64_t grid = tn.xcd_remap ? 8 * ((nblocks + 7) / 8) : nblocks;
+    const int64_t grid = nfull + (tail_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
     if (grid > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((step_kernel<GT, XT, VEC, SUB, MOM, APPLY, OUT>), dim3((unsigned)grid), dim3(kBlock), 0, s, a,
-                       nfull, nblocks, tn.xcd_remap);
+    (void)hipGetLastError();                 // a stale error of an earlier, unrelated call is not this launch's
+    hipLaunchKernelGGL((step_kernel<GT, XT, VEC, SUB, MOM, APPLY, OUT, SERIAL>), dim3((unsigned)grid), dim3(kBlock), 0,
+                       s, a, nfull);
     return hipGetLastError();
 }
 
-template <typename GT, typename XT, int VEC, int SUB, bool MOM, bool APPLY>
-static hipError_t launch_one(const StepArgs& a, hipStream_t s) {
-    const bool out = a.signs_out != nullptr || a.vote_out != nullptr || a.has_flip;
-    if constexpr (!APPLY) return launch_out<GT, XT, VEC, SUB, MOM, APPLY, true>(a, s);   // pack-only forms
-    else return out ? launch_out<GT, XT, VEC, SUB, MOM, APPLY, true>(a, s)
-                    : launch_out<GT, XT, VEC, SUB, MOM, APPLY, false>(a, s);
+template <typename GT, typename XT, int VEC, bool MOM, bool APPLY, bool OUT>
+static hipError_t launch_serial(const StepArgs& a, hipStream_t s) {
+    // One row load in flight per wave where the kernel also writes momentum back (see drain_memory_ops);
+    // SSV_TUNE_STEP_SERIAL=0 switches that off for A/B measurements.
+    if constexpr (MOM && VEC > 1) {
+        if (tuning().step_serial) return launch_out<GT, XT, VEC, MOM, APPLY, OUT, true>(a, s);
+    }
+    return launch_out<GT, XT, VEC, MOM, APPLY, OUT, false>(a, s);
 }
 
-template <typename GT, int VEC, int SUB>
+template <typename GT, typename XT, int VEC, bool MOM, bool APPLY>
+static hipError_t launch_one(const StepArgs& a, hipStream_t s) {
+    const bool out = a.signs_out != nullptr || a.vote_out != nullptr || a.has_flip;
+    if constexpr (!APPLY) return launch_serial<GT, XT, VEC, MOM, APPLY, true>(a, s);   // pack-only forms
+    else return out ? launch_serial<GT, XT, VEC, MOM, APPLY, true>(a, s)
+                    : launch_serial<GT, XT, VEC, MOM, APPLY, false>(a, s);
+}
+
+template <typename GT, int VEC>
 static hipError_t launch_g(const StepArgs& a, int x_dt, hipStream_t s) {
     const bool mom = a.v != nullptr;
     const bool apply = a.x != nullptr;
     if (!apply) {
-        return mom ? launch_one<GT, float, VEC, SUB, true, false>(a, s)
-                   : launch_one<GT, float, VEC, SUB, false, false>(a, s);
+        return mom ? launch_one<GT, float, VEC, true, false>(a, s) : launch_one<GT, float, VEC, false, false>(a, s);
     }
     if (x_dt == 0) {
-        return mom ? launch_one<GT, float, VEC, SUB, true, true>(a, s)
-                   : launch_one<GT, float, VEC, SUB, false, true>(a, s);
+        return mom ? launch_one<GT, float, VEC, true, true>(a, s) : launch_one<GT, float, VEC, false, true>(a, s);
     }
-    return mom ? launch_one<GT, bf16, VEC, SUB, true, true>(a, s) : launch_one<GT, bf16, VEC, SUB, false, true>(a, s);
+    return mom ? launch_one<GT, bf16, VEC, true, true>(a, s) : launch_one<GT, bf16, VEC, false, true>(a, s);
 }
 
 hipError_t launch_step(const StepArgs& a, int g_dt, int x_dt, bool vector_ok, hipStream_t s) {
-    const int sub = tuning().step_sub;
-    if (g_dt == 0) {
-        if (!vector_ok) return launch_g<float, 1, 4>(a, x_dt, s);
-        if (sub == 1) return launch_g<float, 4, 1>(a, x_dt, s);
-        if (sub == 2) return launch_g<float, 4, 2>(a, x_dt, s);
-        return launch_g<float, 4, 4>(a, x_dt, s);
-    }
-    if (!vector_ok) return launch_g<bf16, 1, 4>(a, x_dt, s);
+    if (g_dt == 0) return vector_ok ? launch_g<float, 4>(a, x_dt, s) : launch_g<float, 1>(a, x_dt, s);
     // bf16 gradients also use 4 coordinates per lane (8-byte g pieces, 16-byte v pieces): every
     // momentum access of a wave is then one contiguous KiB.  With 8 per lane the two 16-byte v
     // pieces of a lane interleave with its neighbours' and the step runs at 65% instead of 76%.
-    if (sub == 1) return launch_g<bf16, 4, 1>(a, x_dt, s);
-    if (sub == 2) return launch_g<bf16, 4, 2>(a, x_dt, s);
-    return launch_g<bf16, 4, 4>(a, x_dt, s);
+    return vector_ok ? launch_g<bf16, 4>(a, x_dt, s) : launch_g<bf16, 1>(a, x_dt, s);
 }
 
 }  // namespace ssv

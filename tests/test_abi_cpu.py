@@ -91,6 +91,57 @@ def test_binding_refuses_cpu_tensors():
         sv.sign_pack(torch.zeros(2, 64))
 
 
+def test_binding_checks_every_buffer_against_M_and_d_before_the_call():
+    # shapes are validated before anything touches the device, so CPU tensors suffice to reach the checks:
+    # a buffer that cannot hold M rows of d bits / d weights must never reach a kernel that would write past it
+    import torch
+    import paper_1810_05291_amd as sv
+    M, d = 3, 1000
+    W = sv.words_for(d)
+    g = torch.zeros(M, d)
+    v = torch.zeros(M, d)
+    x = torch.zeros(d)
+    rows = torch.zeros(M, W, dtype=torch.int64)
+    vote = torch.zeros(W, dtype=torch.int64)
+
+    def rejected(match, fn, *a, **k):
+        with pytest.raises(ValueError, match=match):
+            fn(*a, **k)
+
+    # vote_apply: x shorter than d, d beyond the packed rows, short / mistyped vote_out
+    rejected("x has", sv.vote_apply, rows, d, x[:-1], 1e-3)
+    rejected("rows hold", sv.vote_apply, rows, 64 * W + 1, torch.zeros(64 * W + 1), 1e-3)
+    rejected("vote_out holds", sv.vote_apply, rows, d, x, 1e-3, vote_out=vote[:-1])
+    rejected("int64", sv.vote_apply, rows, d, x, 1e-3, vote_out=vote.to(torch.int32))
+    rejected("int64", sv.vote_apply, rows.to(torch.int32), d, x, 1e-3)
+    rejected("positive", sv.vote_apply, rows, 0, x, 1e-3)
+    # apply_sign_update: vote must hold words_for(x.numel()) words
+    rejected("vote holds", sv.apply_sign_update, x, vote[:-1], 1e-3)
+    rejected("int64", sv.apply_sign_update, x, vote.to(torch.float64), 1e-3)
+    rejected("contiguous", sv.apply_sign_update, torch.zeros(2 * d)[::2], vote, 1e-3)
+    # majority_vote: d against the row width, vote size
+    rejected("rows hold", sv.majority_vote, rows, 64 * W + 1)
+    rejected("vote holds", sv.majority_vote, rows, d, vote[:-1])
+    rejected("2-D", sv.majority_vote, vote, d)
+    # sign_pack / signum_momentum_pack: a supplied signs buffer must have M rows of enough words
+    rejected("rows, expected", sv.sign_pack, g, rows[:2])
+    rejected("rows hold", sv.sign_pack, g, rows[:, :-1])
+    rejected("rows hold", sv.signum_momentum_pack, g, v, 0.9, rows[:, :-1])
+    rejected("v must be", sv.signum_momentum_pack, g, v[:2], 0.9)
+    # signum_step: x, vote_out, signs_out, worker_flip
+    rejected("x has", sv.signum_step, g, v, 0.9, x[:-1], 1e-3)
+    rejected("vote_out holds", sv.signum_step, g, v, 0.9, x, 1e-3, vote_out=vote[:-1])
+    rejected("contiguous", sv.signum_step, g, v, 0.9, x, 1e-3, vote_out=torch.zeros(2 * W, dtype=torch.int64)[::2])
+    rejected("int64", sv.signum_step, g, v, 0.9, x, 1e-3, vote_out=vote.to(torch.int16))
+    rejected("rows, expected", sv.signum_step, g, v, 0.9, x, 1e-3, signs_out=rows[:2])
+    rejected("rows hold", sv.signum_step, g, v, 0.9, x, 1e-3, signs_out=rows[:, :-1])
+    rejected("contiguous rows", sv.signum_step, g, v, 0.9, x, 1e-3, signs_out=torch.zeros(W, M, dtype=torch.int64).T)
+    rejected("worker_flip", sv.signum_step, g, v, 0.9, x, 1e-3, worker_flip=[1, 0])
+    # well-formed arguments get as far as the device check (and stop there: no CPU path exists)
+    rejected("GPU memory only", sv.signum_step, g, v, 0.9, x, 1e-3, vote_out=vote, signs_out=rows)
+    rejected("GPU memory only", sv.vote_apply, rows, d, x, 1e-3, vote_out=vote)
+
+
 def test_product_package_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_1810_05291_amd")
     for dirpath, _, files in os.walk(pkg):

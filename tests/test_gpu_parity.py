@@ -339,6 +339,130 @@ def test_step_special_values_do_not_spread(sv):
     assert np.isfinite(wl.to_numpy(x)).all()
 
 
+def _bf16_tensor(bits):
+    """device bf16 tensor from uint16 bit patterns"""
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(DEV).view(torch.bfloat16)
+
+
+def _same_up_to_nan_payload_bf16(got, ref):
+    nan_g, nan_r = np.isnan(ora.bf16_to_f32(got)), np.isnan(ora.bf16_to_f32(ref))
+    return np.array_equal(nan_g, nan_r) and np.array_equal(got[~nan_r], ref[~nan_r])
+
+
+def test_step_special_values_bf16(sv):
+    # bf16 gradients AND bf16 weights holding +-Inf, NaN, +-0 and bf16 denormals: a faulty worker is one vote,
+    # and a weight that is already Inf / NaN stays what IEEE arithmetic makes of it, identically on both sides
+    M, d = 5, 2048
+    rng = np.random.default_rng(5)
+    g_bits = ora.f32_to_bf16((rng.standard_normal((M, d)) * 1e-2).astype(np.float32))
+    g_bits[0, :256] = 0x7F80          # +Inf
+    g_bits[0, 256:512] = 0xFF80       # -Inf
+    g_bits[0, 512:768] = 0x7FC0       # NaN
+    g_bits[3, 512:640] = 0xFFC1       # NaN with the sign bit set
+    g_bits[1, ::3] = 0x0000           # +0
+    g_bits[2, ::5] = 0x8000           # -0
+    g_bits[4, 1024:1280] = 0x0001     # smallest positive bf16 denormal
+    g_bits[4, 1280:1536] = 0x8001     # and its negative
+    x_bits = ora.f32_to_bf16((rng.standard_normal(d) * 0.02).astype(np.float32))
+    x_bits[100:110] = 0x7F80
+    x_bits[110:120] = 0xFF80
+    x_bits[120:130] = 0x7FC0
+    x_bits[130:140] = 0x0000
+    x_bits[140:150] = 0x8000
+    x_bits[150:160] = 0x0001
+    x_bits[160:170] = 0x7F7F          # largest finite bf16: the step must not overflow it by rounding
+    for wd in (0.0, 0.01):
+        g, x = _bf16_tensor(g_bits), _bf16_tensor(x_bits)
+        v = torch.zeros((M, d), device=DEV)
+        x_ref, v_ref = x_bits.copy(), np.zeros((M, d), np.float32)
+        W = sv.words_for(d)
+        vote = torch.empty((W,), dtype=torch.int64, device=DEV)
+        signs = torch.empty((M, W), dtype=torch.int64, device=DEV)
+        for step in range(2):
+            sv.signum_step(g, v, 0.9, x, 1e-3, wd, vote_out=vote, signs_out=signs)
+            torch.cuda.synchronize()
+            vote_ref, signs_ref = ora.signum_step(g_bits, v_ref, 0.9, x_ref, 1e-3, wd, want_signs=True)
+            assert np.array_equal(wl.to_numpy(signs), signs_ref), f"signs, step {step}"
+            assert np.array_equal(wl.to_numpy(vote), vote_ref), f"vote, step {step}"
+            assert _same_up_to_nan_payload_bf16(wl.to_numpy(x), x_ref), f"weights, step {step}"
+            v_gpu = wl.to_numpy(v)
+            nan = np.isnan(v_ref)
+            assert np.array_equal(np.isnan(v_gpu), nan) and np.array_equal(v_gpu[~nan], v_ref[~nan])
+        # the unfused update from the same vote sees the same special weights
+        x2 = _bf16_tensor(x_bits)
+        x2_ref = x_bits.copy()
+        sv.apply_sign_update(x2, vote, 1e-3, wd)
+        torch.cuda.synchronize()
+        ora.apply_sign_update(x2_ref, vote_ref, 1e-3, wd)
+        assert _same_up_to_nan_payload_bf16(wl.to_numpy(x2), x2_ref)
+        # fp32 weights with the same specials through the stand-alone update and the fused vote + update
+        x32_h = ora.bf16_to_f32(x_bits)
+        for fn in ("apply", "vote_apply"):
+            x32 = torch.from_numpy(x32_h.copy()).to(DEV)
+            x32_ref = x32_h.copy()
+            if fn == "apply":
+                sv.apply_sign_update(x32, vote, 1e-3, wd)
+            else:
+                sv.vote_apply(signs, d, x32, 1e-3, wd)
+            torch.cuda.synchronize()
+            ora.apply_sign_update(x32_ref, vote_ref, 1e-3, wd)
+            got = wl.to_numpy(x32)
+            nan = np.isnan(x32_ref)
+            assert np.array_equal(np.isnan(got), nan) and np.array_equal(got[~nan], x32_ref[~nan]), fn
+
+
+@pytest.mark.parametrize("g_kind", ["f32", "bf16"])
+def test_denormal_momentum_is_not_flushed(sv, g_kind):
+    # gradients so small that (1-beta) g and fma(beta, v, .) are fp32 denormals, of both signs: the sign of a
+    # denormal is data (a flushed negative denormal would read as -0 and vote +1).  Signs, the bits of v and the
+    # vote must equal the oracle's; the oracle runs on an x86 host, which keeps denormals.
+    M, d = 7, 70_003
+    rng = np.random.default_rng(11)
+    W = sv.words_for(d)
+    v = torch.zeros((M, d), device=DEV)
+    v_ref = np.zeros((M, d), np.float32)
+    x = wl.gaussian((d,), 0.02, seed=3, device=DEV)
+    x_ref = wl.to_numpy(x).copy()
+    x_lean, v_lean = x.clone(), v.clone()
+    seen_denormal = False
+    for step in range(3):
+        if g_kind == "f32":
+            # magnitudes 1e-44 .. 1e-38: denormal or barely normal; products with 0.1 are all denormal
+            mag = (10.0 ** rng.uniform(-44, -38, size=(M, d)))
+            g_h = (np.where(rng.random((M, d)) < 0.5, -1.0, 1.0) * mag).astype(np.float32)
+            g = torch.from_numpy(g_h).to(DEV)
+        else:
+            # bf16 denormals (exponent field 0, any mantissa) and the smallest normals, both signs
+            g_h = (rng.integers(1, 0x0100, size=(M, d)).astype(np.uint16)
+                   | (rng.integers(0, 2, size=(M, d)).astype(np.uint16) << 15))
+            g = _bf16_tensor(g_h)
+        assert np.array_equal(wl.to_numpy(g), g_h), "the device copy must hold the denormals"
+        vote = torch.empty((W,), dtype=torch.int64, device=DEV)
+        signs = torch.empty((M, W), dtype=torch.int64, device=DEV)
+        sv.signum_step(g, v, 0.9, x, 1e-4, vote_out=vote, signs_out=signs)
+        sv.signum_step(g, v_lean, 0.9, x_lean, 1e-4)                       # lean form
+        torch.cuda.synchronize()
+        vote_ref, signs_ref = ora.signum_step(g_h, v_ref, 0.9, x_ref, 1e-4, want_signs=True)
+        tiny = np.finfo(np.float32).tiny
+        frac = ((np.abs(v_ref) < tiny) & (v_ref != 0)).mean()
+        seen_denormal |= frac > 0.5
+        assert np.array_equal(wl.to_numpy(v), v_ref), f"momentum bits differ at step {step}"
+        assert np.array_equal(wl.to_numpy(signs), signs_ref), f"signs differ at step {step}"
+        assert np.array_equal(wl.to_numpy(vote), vote_ref), f"vote differs at step {step}"
+        assert np.array_equal(wl.to_numpy(x), x_ref)
+        assert torch.equal(v_lean, v) and torch.equal(x_lean, x)
+        # and through the unfused momentum + pack entry point from the same state
+        if step == 0:
+            v2 = torch.zeros((M, d), device=DEV)
+            s2 = sv.signum_momentum_pack(g, v2, 0.9)
+            torch.cuda.synchronize()
+            assert np.array_equal(wl.to_numpy(s2), signs_ref) and np.array_equal(wl.to_numpy(v2), v_ref)
+    assert seen_denormal, "the test did not reach the denormal range"
+    negative_denormals = int(((v_ref < 0) & (np.abs(v_ref) < np.finfo(np.float32).tiny)).sum())
+    _log(f"denormal momentum ({g_kind}): {negative_denormals} negative denormal entries kept their sign")
+    assert negative_denormals > 1000
+
+
 def test_argument_errors_leave_buffers_untouched(sv):
     lib = sv.load_library()
     d, M = 1000, 3

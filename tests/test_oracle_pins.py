@@ -485,6 +485,63 @@ def test_whole_step_against_numpy_float64(M, d, beta, wd):
     assert np.array_equal(vote_f, vote) and np.array_equal(x_f, x_o)
 
 
+@pytest.mark.parametrize("g_dtype", [np.float32, np.uint16])
+def test_composites_respect_gradient_and_momentum_row_strides(g_dtype):
+    # rows that sit in wider buffers (row stride != d, different for g, v and the packed signs): the result must
+    # equal the float64 numpy restatement row by row, and nothing outside the rows may be read as data or written
+    M, d, beta, lr = 5, 203, 0.75, 1e-3
+    g32 = (RNG.standard_normal(d) * 1e-3 + RNG.standard_normal((M, d)) * 1e-2).astype(np.float32)
+    if g_dtype == np.uint16:
+        g_rows = ora.f32_to_bf16(g32)
+        g32 = ora.bf16_to_f32(g_rows)
+    else:
+        g_rows = g32
+    gbuf = np.full((M, d + 37), 0x7FC1 if g_dtype == np.uint16 else np.nan, dtype=g_dtype)   # NaN pads: must never be read
+    gbuf[:, :d] = g_rows
+    vbuf = np.full((M, d + 11), 123.0, np.float32)
+    vbuf[:, :d] = (RNG.standard_normal((M, d)) * 3e-3).astype(np.float32)
+    v0 = vbuf[:, :d].copy()
+    x = (RNG.standard_normal(d) * 0.02).astype(np.float32)
+    v_ref, s_ref, vote_ref, x_ref = _numpy_step(g32, v0, beta, x, lr, 0.0)
+    decided = np.abs(v_ref) > 1e-6 * np.abs(v_ref).max()
+    assert decided.all()
+
+    W = ora.words_for(d)
+    sbuf = np.full((M, W + 2), np.uint64(0xFFFFFFFFFFFFFFFF))
+    ora.signum_momentum_pack(gbuf[:, :d], vbuf[:, :d], beta, signs=sbuf[:, :W])
+    assert (vbuf[:, d:] == 123.0).all() and (sbuf[:, W:] == np.uint64(0xFFFFFFFFFFFFFFFF)).all()
+    scale = np.abs((1 - beta) * g32) + np.abs(beta * v0)
+    assert (np.abs(vbuf[:, :d] - v_ref) <= 1e-6 * scale).all()
+    for m in range(M):
+        assert np.array_equal(ora.unpack_signs(np.ascontiguousarray(sbuf[m, :W]), d), s_ref[m])
+
+    vbuf2 = np.full((M, d + 5), -7.0, np.float32)
+    vbuf2[:, :d] = v0
+    x_o = x.copy()
+    vote, signs = ora.signum_step(gbuf[:, :d], vbuf2[:, :d], beta, x_o, lr, want_signs=True)
+    assert (vbuf2[:, d:] == -7.0).all()
+    assert np.array_equal(vbuf2[:, :d], vbuf[:, :d])
+    assert np.array_equal(signs, np.ascontiguousarray(sbuf[:, :W]))
+    assert np.array_equal(ora.unpack_signs(vote, d), vote_ref)
+    assert np.allclose(x_o, x_ref, rtol=1e-6, atol=1e-12)
+
+
+def test_bf16_nan_keeps_sign_and_payload_and_gets_the_quiet_bit():
+    # reading R5: a NaN is not rounded like a number (adding the rounding increment could carry into the
+    # exponent and give Inf or flip the sign); its top 16 bits are kept and the quiet bit is set
+    pat = np.array([0x7F800001, 0x7FC00000, 0xFF800001, 0xFFFFFFFF, 0x7FBFFFFF, 0x7F80FFFF, 0xFFC12345], np.uint32)
+    out = ora.f32_to_bf16(pat.view(np.float32))
+    assert np.array_equal(out, ((pat >> 16) | 0x40).astype(np.uint16))
+    assert np.isnan(ora.bf16_to_f32(out)).all()
+    assert np.array_equal(out >> 15, (pat >> 31).astype(np.uint16))           # sign kept
+    # torch's cast agrees on NaN-ness (its payload convention is its own)
+    t = torch.from_numpy(pat.view(np.float32).copy()).to(torch.bfloat16)
+    assert torch.isnan(t).all()
+    # and the infinities next to them are numbers: exact
+    inf = np.array([np.inf, -np.inf], np.float32)
+    assert np.array_equal(ora.f32_to_bf16(inf), np.array([0x7F80, 0xFF80], np.uint16))
+
+
 def test_resume_is_bit_exact():
     M, d = 5, 2000
     mu = (RNG.standard_normal(d) * 1e-3).astype(np.float32)
