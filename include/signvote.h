@@ -46,6 +46,7 @@
 #ifndef SIGNVOTE_H
 #define SIGNVOTE_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -130,6 +131,37 @@ int ssv_signum_step(const void* g, int g_dt, float* v, int M, int64_t d,
                     void* x, int x_dt, float lr, float weight_decay,
                     uint64_t* vote_out, uint64_t* signs_out, int64_t signs_row_stride_words,
                     const uint8_t* worker_flip, void* stream);
+
+/*
+ * Multi-tensor form of ssv_signum_step (Section 4: fusing many small tensors into one operation saved
+ * compression and communication cost).  A model's parameters are T separate tensors, and every worker's
+ * gradient and momentum of a tensor may be an allocation of its own (where autograd left it).  One launch
+ * runs Algorithm 1 over all of them: the index space is the concatenation of the tensors, each cut into
+ * units of 4096 coordinates with its own ragged end, so no gradient is copied into a flat buffer.  The
+ * result for every tensor equals ssv_signum_step on that tensor alone (without optional outputs).
+ *
+ * The tensors are described by a "plan", a block of bytes that holds only sizes, the device addresses given
+ * here and byte offsets, so the same bytes serve on the host and on the device:
+ *   1. size it:  bytes = ssv_multi_plan_bytes(T, M, n)            (0 = bad arguments)
+ *   2. fill a HOST buffer of that size (8-byte aligned) with ssv_multi_plan_fill;
+ *   3. copy the bytes to DEVICE memory (8-byte aligned) once; both copies stay owned by the caller and must
+ *      stay unchanged while steps use them;
+ *   4. every iteration: ssv_signum_step_multi(plan_host, plan_device, beta, lr, weight_decay, stream).
+ *
+ *   T        number of tensors (>= 1);  M workers;  n[t] >= 1 elements of tensor t, sum <= SSV_MAX_COORDS   (host array)
+ *   x[t]     device address of tensor t's weights (x_dt)                                             (host array of T)
+ *   g[t*M+m] device address of worker m's gradient of tensor t (g_dt, n[t] elements)                  (host array of T*M)
+ *   v[t*M+m] device address of worker m's fp32 momentum of tensor t; v == NULL: signSGD, beta must be 0
+ * Addresses must be aligned to their element size (else SSV_ERR_ALIGN); a tensor all of whose addresses are
+ * 16-byte aligned (8-byte for bf16) takes the vector path, others a one-element-per-lane path with the same
+ * results.  plan_fill touches no device memory; step_multi reads T, M and the layout from plan_host before
+ * it returns, and its kernel reads the tables from plan_device.
+ */
+size_t ssv_multi_plan_bytes(int T, int M, const int64_t* n);
+int ssv_multi_plan_fill(void* plan_host, size_t plan_bytes, int T, int M, const int64_t* n, void* const* x, int x_dt,
+                        const void* const* g, int g_dt, float* const* v);
+int ssv_signum_step_multi(const void* plan_host, const void* plan_device, float beta, float lr, float weight_decay,
+                          void* stream);
 
 /* Static, NUL-terminated description of a status code (host memory, never freed). */
 const char* ssv_status_string(int status);

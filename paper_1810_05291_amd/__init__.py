@@ -21,5 +21,7 @@ from .binding import (  # noqa: F401
     status_string,
     version,
     bench_copy,
+    MultiTensorPlan,
+    signum_step_multi,
 )
-from .optim import FlatLayout, SignumMajorityVote  # noqa: F401,E402
+from .optim import FlatLayout, SignumMajorityVote, SignumMajorityVoteMulti  # noqa: F401,E402

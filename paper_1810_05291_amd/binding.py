@@ -54,6 +54,12 @@ def load_library():
             fn = getattr(lib, name)
             fn.argtypes = argtypes
             fn.restype = _c_int
+        lib.ssv_multi_plan_bytes.argtypes = [_c_int, _c_int, _c_p]
+        lib.ssv_multi_plan_bytes.restype = ctypes.c_size_t
+        lib.ssv_multi_plan_fill.argtypes = [_c_p, ctypes.c_size_t, _c_int, _c_int, _c_p, _c_p, _c_int, _c_p, _c_int, _c_p]
+        lib.ssv_multi_plan_fill.restype = _c_int
+        lib.ssv_signum_step_multi.argtypes = [_c_p, _c_p, _c_f, _c_f, _c_f, _c_p]
+        lib.ssv_signum_step_multi.restype = _c_int
         lib.ssv_status_string.argtypes = [_c_int]
         lib.ssv_status_string.restype = ctypes.c_char_p
         lib.ssv_version.argtypes = []
@@ -250,6 +256,65 @@ def signum_step(g, v, beta, x, lr, weight_decay=0.0, vote_out=None, signs_out=No
                                           float(lr), float(weight_decay), _ptr(vote_out), _ptr(signs_out), ss,
                                           ctypes.cast(flip, _c_p) if flip is not None else None, _stream(dev)))
     return x
+
+
+class MultiTensorPlan:
+    """The plan of ssv_signum_step_multi for T weight tensors and M workers' gradient (and momentum) tensors.
+
+    params[t]      weight tensor t (contiguous, fp32 or bf16, one dtype for all)
+    grads[m][t]    worker m's gradient of tensor t (contiguous, same number of elements, one dtype for all)
+    momenta[m][t]  worker m's fp32 momentum of tensor t, or momenta=None for signSGD
+    The tensors are referenced (kept alive), not copied; the plan holds their addresses, so they must not be
+    reallocated while the plan is in use.  The device copy of the plan is made here, once."""
+
+    def __init__(self, params, grads, momenta=None):
+        lib = load_library()
+        T, M = len(params), len(grads)
+        if T < 1 or M < 1:
+            raise ValueError("need at least one tensor and one worker")
+        if any(len(row) != T for row in grads) or (momenta is not None and
+                                                  (len(momenta) != M or any(len(row) != T for row in momenta))):
+            raise ValueError("grads and momenta must be M lists of T tensors")
+        dev = _dev(*params, *[t for row in grads for t in row], *([t for row in momenta for t in row] if momenta else []))
+        x_dt, g_dt = _dt(params[0]), _dt(grads[0][0])
+        n = (ctypes.c_int64 * T)()
+        xs = (ctypes.c_void_p * T)()
+        gs = (ctypes.c_void_p * (T * M))()
+        vs = (ctypes.c_void_p * (T * M))() if momenta is not None else None
+        for t, p in enumerate(params):
+            if not p.is_contiguous() or _dt(p) != x_dt or p.numel() < 1:
+                raise ValueError("weight tensors must be contiguous, non-empty and of one dtype")
+            n[t] = p.numel()
+            xs[t] = p.data_ptr()
+            for m in range(M):
+                gt = grads[m][t]
+                if not gt.is_contiguous() or _dt(gt) != g_dt or gt.numel() != p.numel():
+                    raise ValueError(f"gradient of worker {m}, tensor {t}: must be contiguous, {p.numel()} elements, one dtype")
+                gs[t * M + m] = gt.data_ptr()
+                if momenta is not None:
+                    vt = momenta[m][t]
+                    if not vt.is_contiguous() or vt.dtype != torch.float32 or vt.numel() != p.numel():
+                        raise ValueError(f"momentum of worker {m}, tensor {t}: must be contiguous fp32, {p.numel()} elements")
+                    vs[t * M + m] = vt.data_ptr()
+        nbytes = lib.ssv_multi_plan_bytes(T, M, ctypes.cast(n, _c_p))
+        if nbytes == 0:
+            raise ValueError("bad tensor list (sizes out of range)")
+        self.host = torch.zeros((nbytes + 7) // 8, dtype=torch.int64)            # 8-byte aligned host bytes
+        _check("ssv_multi_plan_fill",
+               lib.ssv_multi_plan_fill(self.host.data_ptr(), nbytes, T, M, ctypes.cast(n, _c_p), ctypes.cast(xs, _c_p),
+                                       x_dt, ctypes.cast(gs, _c_p), g_dt,
+                                       ctypes.cast(vs, _c_p) if vs is not None else None))
+        self.device = self.host.to(dev)
+        self.T, self.M, self.numel, self.nbytes, self.dev = T, M, sum(int(k) for k in n), int(nbytes), dev
+        self.has_momentum = momenta is not None
+        self._keep = (list(params), [list(r) for r in grads], None if momenta is None else [list(r) for r in momenta])
+
+
+def signum_step_multi(plan, beta, lr, weight_decay=0.0):
+    """One fused iteration of Algorithm 1 over all tensors of the plan, in one launch."""
+    _check("ssv_signum_step_multi",
+           load_library().ssv_signum_step_multi(plan.host.data_ptr(), plan.device.data_ptr(), float(beta), float(lr),
+                                                float(weight_decay), _stream(plan.dev)))
 
 
 def bench_copy(src, dst):

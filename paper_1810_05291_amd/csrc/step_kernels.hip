@@ -19,129 +19,9 @@
 // write v) plus 8 per coordinate for x at fp32.  Per group of U = 2 workers a wave reads its
 // 2*U*SUB row pieces one at a time (each load waits for the one before), then computes and issues
 // the U*SUB momentum stores back to back: a read phase and a write burst per group.
-#include "device_utils.h"
+#include "step_tiles.h"
 
 namespace ssv {
-
-template <typename GT, int VEC, int SUB, bool MOM, bool OUT, bool GUARD, bool SERIAL, int U>
-__device__ __forceinline__ void worker_group(const StepArgs& a, int m0, int64_t j0, const int (&nvalid)[SUB],
-                                             int lane, int64_t tile0, uint32_t (&cnt)[SUB][VEC]) {
-    constexpr int64_t kTile = (int64_t)kWave * VEC * kWavesPerBlock;   // a wave's tiles are a block-row apart
-    // SERIAL: one row load in flight per wave.  Chosen by the launcher where momentum is written back
-    // (read/write mix); the read-only forms (sign_pack, signSGD step) keep all loads of the group in flight.
-    float gv[U][SUB][VEC];
-    float vv[U][SUB][VEC];
-    const GT* __restrict__ g = static_cast<const GT*>(a.g);
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const GT* gp = g + (int64_t)(m0 + u) * a.g_stride + j0;
-#pragma unroll
-        for (int s = 0; s < SUB; ++s) {
-            if constexpr (GUARD) {
-                load_vals_guarded<GT, VEC>(gp + s * kTile, nvalid[s], gv[u][s]);
-            } else {
-                load_vals<VEC>(gp + s * kTile, gv[u][s]);
-                if constexpr (SERIAL) drain_memory_ops();
-            }
-        }
-    }
-    if constexpr (MOM) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const float* vp = a.v + (int64_t)(m0 + u) * a.v_stride + j0;
-#pragma unroll
-            for (int s = 0; s < SUB; ++s) {
-                if constexpr (GUARD) {
-                    load_vals_guarded<float, VEC>(vp + s * kTile, nvalid[s], vv[u][s]);
-                } else {
-                    load_vals<VEC>(vp + s * kTile, vv[u][s]);
-                    if constexpr (SERIAL) drain_memory_ops();
-                }
-            }
-        }
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int m = m0 + u;
-        uint32_t flip = 0u;
-        if constexpr (OUT) flip = a.has_flip ? ((a.flip.w[m >> 5] >> (m & 31)) & 1u) : 0u;
-#pragma unroll
-        for (int s = 0; s < SUB; ++s) {
-            if constexpr (MOM) {
-#pragma unroll
-                for (int c = 0; c < VEC; ++c) {
-                    float t = a.omb * gv[u][s][c];
-                    vv[u][s][c] = fmaf(a.beta, vv[u][s][c], t);
-                }
-                float* vp = a.v + (int64_t)m * a.v_stride + j0 + s * kTile;
-                if constexpr (GUARD) store_vals_guarded<float, VEC>(vp, nvalid[s], vv[u][s]);
-                else store_vals<VEC>(vp, vv[u][s]);
-            } else {
-#pragma unroll
-                for (int c = 0; c < VEC; ++c) vv[u][s][c] = gv[u][s][c];
-            }
-            uint32_t b[VEC];
-#pragma unroll
-            for (int c = 0; c < VEC; ++c) {
-                b[c] = (vv[u][s][c] >= 0.0f ? 1u : 0u) ^ flip;
-                if constexpr (GUARD) b[c] = (c < nvalid[s]) ? b[c] : 0u;
-                cnt[s][c] += b[c];
-            }
-            if (OUT && a.signs_out != nullptr)
-                pack_store_tile<VEC>(a.signs_out + (int64_t)m * a.signs_stride, tile0 + s * kWavesPerBlock, a.W, lane, b);
-        }
-    }
-}
-
-// tile0 = index of the wave's first tile of 64*VEC coordinates; its s-th tile is tile0 + 4 s
-template <typename GT, typename XT, int VEC, int SUB, bool MOM, bool APPLY, bool OUT, bool GUARD, bool SERIAL>
-__device__ __forceinline__ void step_tiles(const StepArgs& a, int64_t tile0, int lane) {
-    constexpr int64_t kTile = (int64_t)kWave * VEC * kWavesPerBlock;
-    const int64_t j0 = tile0 * (int64_t)(kWave * VEC) + (int64_t)lane * VEC;
-    int nvalid[SUB];
-#pragma unroll
-    for (int s = 0; s < SUB; ++s) {
-        nvalid[s] = VEC;
-        if constexpr (GUARD) {
-            int64_t r = a.d - (j0 + s * kTile);
-            nvalid[s] = r >= VEC ? VEC : (r > 0 ? (int)r : 0);
-        }
-    }
-    uint32_t cnt[SUB][VEC];
-#pragma unroll
-    for (int s = 0; s < SUB; ++s)
-#pragma unroll
-        for (int c = 0; c < VEC; ++c) cnt[s][c] = 0;
-
-    constexpr int U = 2;
-    int m = 0;
-    for (; m + U <= a.M; m += U)
-        worker_group<GT, VEC, SUB, MOM, OUT, GUARD, SERIAL, U>(a, m, j0, nvalid, lane, tile0, cnt);
-    if (m < a.M) worker_group<GT, VEC, SUB, MOM, OUT, GUARD, SERIAL, 1>(a, m, j0, nvalid, lane, tile0, cnt);
-
-#pragma unroll
-    for (int s = 0; s < SUB; ++s) {
-        uint32_t vb[VEC];
-#pragma unroll
-        for (int c = 0; c < VEC; ++c) {
-            vb[c] = (cnt[s][c] >= (uint32_t)a.T) ? 1u : 0u;
-            if constexpr (GUARD) vb[c] = (c < nvalid[s]) ? vb[c] : 0u;
-        }
-        if (OUT && a.vote_out != nullptr) pack_store_tile<VEC>(a.vote_out, tile0 + s * kWavesPerBlock, a.W, lane, vb);
-        if constexpr (APPLY) {
-            if (nvalid[s] > 0) {
-                XT* xp = static_cast<XT*>(a.x) + j0 + s * kTile;
-                float xv[VEC];
-                if constexpr (GUARD) load_vals_guarded<XT, VEC>(xp, nvalid[s], xv);
-                else load_vals<VEC>(xp, xv);
-#pragma unroll
-                for (int c = 0; c < VEC; ++c) xv[c] = sign_update(xv[c], vb[c] != 0, a.lr, a.wd);
-                if constexpr (GUARD) store_vals_guarded<XT, VEC>(xp, nvalid[s], xv);
-                else store_vals<VEC>(xp, xv);
-            }
-        }
-    }
-}
 
 // Blocks 0 .. nfull-1 each take 4*SUB consecutive tiles: in step s (s < SUB) the block's four waves
 // touch four adjacent tiles, i.e. one contiguous 4 KiB run of every row.  The waves of the blocks
@@ -159,10 +39,6 @@ __global__ __launch_bounds__(kBlock) void step_kernel(StepArgs a, int64_t nfull)
         if (tile < a.ntiles) step_tiles<GT, XT, VEC, 1, MOM, APPLY, OUT, true, false>(a, tile, lane);
     }
 }
-
-// Tiles a wave of the step kernel holds at once.  4 is the measured optimum on MI355X (1 and 2 cost
-// 3-8% on the resnet50-sized step).
-constexpr int kStepSub = 4;
 
 template <typename GT, typename XT, int VEC, bool MOM, bool APPLY, bool OUT, bool SERIAL>
 static hipError_t launch_out(StepArgs a, hipStream_t s) {

@@ -1,0 +1,154 @@
+// The tile body of the gradient-side kernels: momentum, sign, count over the workers, vote, update for the
+// tiles one wavefront holds.  Shared by the flat-vector kernels (step_kernels.hip) and the multi-tensor
+// kernel (multi_kernels.hip).
+#pragma once
+#include "device_utils.h"
+
+
+namespace ssv {
+
+// Where worker m's row of gradients / momentum starts.  FlatRows: the [M][row_stride] matrices of the flat
+// entry points.  TableRows: a.g / a.v point to M device pointers, one per worker (the multi-tensor entry
+// point, where every worker's gradient of a tensor is an allocation of its own).
+struct FlatRows {
+    template <typename GT>
+    static __device__ __forceinline__ const GT* g(const StepArgs& a, int m) {
+        return static_cast<const GT*>(a.g) + (int64_t)m * a.g_stride;
+    }
+    static __device__ __forceinline__ float* v(const StepArgs& a, int m) { return a.v + (int64_t)m * a.v_stride; }
+};
+struct TableRows {
+    template <typename GT>
+    static __device__ __forceinline__ const GT* g(const StepArgs& a, int m) {
+        return static_cast<const GT* const*>(a.g)[m];
+    }
+    static __device__ __forceinline__ float* v(const StepArgs& a, int m) {
+        return reinterpret_cast<float* const*>(a.v)[m];
+    }
+};
+
+template <typename GT, int VEC, int SUB, bool MOM, bool OUT, bool GUARD, bool SERIAL, typename ROWS, int U>
+__device__ __forceinline__ void worker_group(const StepArgs& a, int m0, int64_t j0, const int (&nvalid)[SUB],
+                                             int lane, int64_t tile0, uint32_t (&cnt)[SUB][VEC]) {
+    constexpr int64_t kTile = (int64_t)kWave * VEC * kWavesPerBlock;   // a wave's tiles are a block-row apart
+    // SERIAL: one row load in flight per wave.  Chosen by the launcher where momentum is written back
+    // (read/write mix); the read-only forms (sign_pack, signSGD step) keep all loads of the group in flight.
+    float gv[U][SUB][VEC];
+    float vv[U][SUB][VEC];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const GT* __restrict__ gp = ROWS::template g<GT>(a, m0 + u) + j0;
+#pragma unroll
+        for (int s = 0; s < SUB; ++s) {
+            if constexpr (GUARD) {
+                load_vals_guarded<GT, VEC>(gp + s * kTile, nvalid[s], gv[u][s]);
+            } else {
+                load_vals<VEC>(gp + s * kTile, gv[u][s]);
+                if constexpr (SERIAL) drain_memory_ops();
+            }
+        }
+    }
+    if constexpr (MOM) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float* vp = ROWS::v(a, m0 + u) + j0;
+#pragma unroll
+            for (int s = 0; s < SUB; ++s) {
+                if constexpr (GUARD) {
+                    load_vals_guarded<float, VEC>(vp + s * kTile, nvalid[s], vv[u][s]);
+                } else {
+                    load_vals<VEC>(vp + s * kTile, vv[u][s]);
+                    if constexpr (SERIAL) drain_memory_ops();
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int m = m0 + u;
+        uint32_t flip = 0u;
+        if constexpr (OUT) flip = a.has_flip ? ((a.flip.w[m >> 5] >> (m & 31)) & 1u) : 0u;
+#pragma unroll
+        for (int s = 0; s < SUB; ++s) {
+            if constexpr (MOM) {
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) {
+                    float t = a.omb * gv[u][s][c];
+                    vv[u][s][c] = fmaf(a.beta, vv[u][s][c], t);
+                }
+                float* vp = ROWS::v(a, m) + j0 + s * kTile;
+                if constexpr (GUARD) store_vals_guarded<float, VEC>(vp, nvalid[s], vv[u][s]);
+                else store_vals<VEC>(vp, vv[u][s]);
+            } else {
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) vv[u][s][c] = gv[u][s][c];
+            }
+            uint32_t b[VEC];
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) {
+                b[c] = (vv[u][s][c] >= 0.0f ? 1u : 0u) ^ flip;
+                if constexpr (GUARD) b[c] = (c < nvalid[s]) ? b[c] : 0u;
+                cnt[s][c] += b[c];
+            }
+            if (OUT && a.signs_out != nullptr)
+                pack_store_tile<VEC>(a.signs_out + (int64_t)m * a.signs_stride, tile0 + s * kWavesPerBlock, a.W, lane, b);
+        }
+    }
+}
+
+// tile0 = index of the wave's first tile of 64*VEC coordinates; its s-th tile is tile0 + 4 s
+template <typename GT, typename XT, int VEC, int SUB, bool MOM, bool APPLY, bool OUT, bool GUARD, bool SERIAL,
+          typename ROWS = FlatRows>
+__device__ __forceinline__ void step_tiles(const StepArgs& a, int64_t tile0, int lane) {
+    constexpr int64_t kTile = (int64_t)kWave * VEC * kWavesPerBlock;
+    const int64_t j0 = tile0 * (int64_t)(kWave * VEC) + (int64_t)lane * VEC;
+    int nvalid[SUB];
+#pragma unroll
+    for (int s = 0; s < SUB; ++s) {
+        nvalid[s] = VEC;
+        if constexpr (GUARD) {
+            int64_t r = a.d - (j0 + s * kTile);
+            nvalid[s] = r >= VEC ? VEC : (r > 0 ? (int)r : 0);
+        }
+    }
+    uint32_t cnt[SUB][VEC];
+#pragma unroll
+    for (int s = 0; s < SUB; ++s)
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) cnt[s][c] = 0;
+
+    constexpr int U = 2;
+    int m = 0;
+    for (; m + U <= a.M; m += U)
+        worker_group<GT, VEC, SUB, MOM, OUT, GUARD, SERIAL, ROWS, U>(a, m, j0, nvalid, lane, tile0, cnt);
+    if (m < a.M) worker_group<GT, VEC, SUB, MOM, OUT, GUARD, SERIAL, ROWS, 1>(a, m, j0, nvalid, lane, tile0, cnt);
+
+#pragma unroll
+    for (int s = 0; s < SUB; ++s) {
+        uint32_t vb[VEC];
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) {
+            vb[c] = (cnt[s][c] >= (uint32_t)a.T) ? 1u : 0u;
+            if constexpr (GUARD) vb[c] = (c < nvalid[s]) ? vb[c] : 0u;
+        }
+        if (OUT && a.vote_out != nullptr) pack_store_tile<VEC>(a.vote_out, tile0 + s * kWavesPerBlock, a.W, lane, vb);
+        if constexpr (APPLY) {
+            if (nvalid[s] > 0) {
+                XT* xp = static_cast<XT*>(a.x) + j0 + s * kTile;
+                float xv[VEC];
+                if constexpr (GUARD) load_vals_guarded<XT, VEC>(xp, nvalid[s], xv);
+                else load_vals<VEC>(xp, xv);
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) xv[c] = sign_update(xv[c], vb[c] != 0, a.lr, a.wd);
+                if constexpr (GUARD) store_vals_guarded<XT, VEC>(xp, nvalid[s], xv);
+                else store_vals<VEC>(xp, xv);
+            }
+        }
+    }
+}
+
+// Tiles a wave of the step kernels holds at once.  4 is the measured optimum on MI355X (1 and 2 cost
+// 3-8% on the resnet50-sized step).
+constexpr int kStepSub = 4;
+
+}  // namespace ssv

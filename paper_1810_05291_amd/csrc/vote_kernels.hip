@@ -175,39 +175,23 @@ __device__ __forceinline__ uint32_t vote_bits_for(uint32_t vt, int off) {
     return w >> (off & 31);
 }
 
-// GUARD = the tile holds the ragged end of the vector: per-element bounds checks.
-template <typename XT, int XV, bool GUARD>
-__device__ __forceinline__ void apply_wave_tile(XT* __restrict__ xt, int64_t left, uint32_t vt, int lane, float lr,
-                                                float wd) {
-    constexpr int kAcc = (kWave * 32) / (kWave * XV);          // accesses that cover the 2048 coordinates
-    constexpr int UA = kAcc < 8 ? kAcc : 8;                    // weight accesses in flight per lane (1..8 measure alike)
-    static_assert(kAcc % UA == 0, "the tile must split into groups of UA accesses");
+// Weight walk of a tile that holds the ragged end of the vector: per-element bounds checks.
+template <typename XT, int XV>
+__device__ __forceinline__ void apply_ragged_tile(XT* __restrict__ xt, int64_t left, uint32_t vt, int lane, float lr,
+                                                  float wd) {
+    constexpr int kAcc = 32 / XV;                              // accesses that cover the 2048 coordinates
+#pragma unroll 4
+    for (int i = 0; i < kAcc; ++i) {
+        const int off = (i * kWave + lane) * XV;
+        const uint32_t bits = vote_bits_for<XV>(vt, off);      // before any per-lane branch
+        const int64_t r = left - off;
+        const int n = r >= XV ? XV : (r > 0 ? (int)r : 0);
+        if (n > 0) {
+            float xv[XV];
+            load_vals_guarded<XT, XV>(xt + off, n, xv);
 #pragma unroll
-    for (int i0 = 0; i0 < kAcc; i0 += UA) {
-        float xv[UA][XV];
-        int n[UA];
-        uint32_t bits[UA];
-#pragma unroll
-        for (int u = 0; u < UA; ++u) {
-            const int off = ((i0 + u) * kWave + lane) * XV;
-            bits[u] = vote_bits_for<XV>(vt, off);
-            n[u] = XV;
-            if constexpr (GUARD) {
-                const int64_t r = left - off;
-                n[u] = r >= XV ? XV : (r > 0 ? (int)r : 0);
-                if (n[u] > 0) load_vals_guarded<XT, XV>(xt + off, n[u], xv[u]);
-            } else {
-                load_vals<XV>(xt + off, xv[u]);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < UA; ++u) {
-            const int off = ((i0 + u) * kWave + lane) * XV;
-            if (GUARD && n[u] == 0) continue;
-#pragma unroll
-            for (int c = 0; c < XV; ++c) xv[u][c] = sign_update(xv[u][c], ((bits[u] >> c) & 1u) != 0, lr, wd);
-            if constexpr (GUARD) store_vals_guarded<XT, XV>(xt + off, n[u], xv[u]);
-            else store_vals<XV>(xt + off, xv[u]);
+            for (int c = 0; c < XV; ++c) xv[c] = sign_update(xv[c], ((bits >> c) & 1u) != 0, lr, wd);
+            store_vals_guarded<XT, XV>(xt + off, n, xv);
         }
     }
 }
@@ -215,9 +199,14 @@ __device__ __forceinline__ void apply_wave_tile(XT* __restrict__ xt, int64_t lef
 // Fused vote + update.  One wavefront per tile of 2048 coordinates (64 dwords of every row); the
 // workgroup size (64 or 256 threads) only groups neighbouring tiles on one CU.
 // XV = weights per lane per access (4 fp32 / 8 bf16; 1 = any alignment).
+// A full tile issues the first half of its weight loads before the row loads, so that they share one
+// memory round trip, and the second half behind the vote arithmetic (measured 1-2% faster than loading
+// the weights after the vote, and than loading all of them first).
 template <int NPL, typename XT, int XV>
 __global__ __launch_bounds__(kBlock) void vote_apply_kernel(VoteArgs a) {
     constexpr int kTileCoords = kWave * 32;
+    constexpr int kAcc = 32 / XV;                      // weight accesses per lane that cover the tile
+    constexpr int kEarly = kAcc / 2;
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t tile = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
     if (tile >= a.ntiles) return;                      // wave-uniform
@@ -226,6 +215,15 @@ __global__ __launch_bounds__(kBlock) void vote_apply_kernel(VoteArgs a) {
     const int64_t dw = tile * kWave + lane;
     const bool have = dw < ndw;
     const uint32_t* __restrict__ p = reinterpret_cast<const uint32_t*>(a.signs) + dw;
+    XT* __restrict__ xt = static_cast<XT*>(a.x) + tile * (int64_t)kTileCoords;
+    const int64_t left = a.d - tile * (int64_t)kTileCoords;      // > 0: the tile exists
+    const bool full = left >= kTileCoords;                        // wave-uniform
+
+    float xv[kAcc][XV];
+    if (full) {
+#pragma unroll
+        for (int i = 0; i < kEarly; ++i) load_vals<XV>(xt + (i * kWave + lane) * XV, xv[i]);
+    }
 
     uint32_t pl[NPL][1];
 #pragma unroll
@@ -242,11 +240,21 @@ __global__ __launch_bounds__(kBlock) void vote_apply_kernel(VoteArgs a) {
     const uint32_t vt = pl[NPL - 1][0] & mask;
     if (a.vote_out != nullptr && have) reinterpret_cast<uint32_t*>(a.vote_out)[dw] = vt;
 
-    // all 64 lanes are still active: nothing above exits or branches per lane around this point
-    XT* __restrict__ xt = static_cast<XT*>(a.x) + tile * (int64_t)kTileCoords;
-    const int64_t left = a.d - tile * (int64_t)kTileCoords;      // > 0: the tile exists
-    if (left >= kTileCoords) apply_wave_tile<XT, XV, false>(xt, left, vt, lane, a.lr, a.wd);
-    else apply_wave_tile<XT, XV, true>(xt, left, vt, lane, a.lr, a.wd);
+    // all 64 lanes are active again here: the cross-lane reads below need every lane
+    if (full) {
+#pragma unroll
+        for (int i = kEarly; i < kAcc; ++i) load_vals<XV>(xt + (i * kWave + lane) * XV, xv[i]);
+#pragma unroll
+        for (int i = 0; i < kAcc; ++i) {
+            const int off = (i * kWave + lane) * XV;
+            const uint32_t bits = vote_bits_for<XV>(vt, off);
+#pragma unroll
+            for (int c = 0; c < XV; ++c) xv[i][c] = sign_update(xv[i][c], ((bits >> c) & 1u) != 0, a.lr, a.wd);
+            store_vals<XV>(xt + off, xv[i]);
+        }
+    } else {
+        apply_ragged_tile<XT, XV>(xt, left, vt, lane, a.lr, a.wd);
+    }
 }
 
 template <int PW, int NPL>

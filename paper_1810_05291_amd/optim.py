@@ -1,10 +1,15 @@
-"""Flat-vector plumbing for real models: the tensor fusion that Section 4 of the paper credits with
-a speed-up of compression and communication.
+"""Plumbing for real models with many parameter tensors: the tensor fusion that Section 4 of the paper
+credits with a speed-up of compression and communication.  Two ways to get one kernel launch per step
+however many tensors the model has:
 
-The library works on one flat vector of d coordinates.  A model has many parameter tensors; this
-module lays them out back to back in one flat buffer ONCE, hands out views for the parameters and
-for each simulated worker's gradients, and calls the fused step on the flat buffers.  No copies are
-made per step, and every step is one kernel launch however many tensors the model has.
+SignumMajorityVote       lays the tensors out back to back in ONE flat buffer, once, and hands out views for
+                         the parameters and for each simulated worker's gradients.  The step itself copies
+                         nothing -- but whoever produces the gradients must write them into those views; a
+                         model whose autograd leaves gradients in tensors of its own pays one copy per
+                         worker per step to move them there.
+SignumMajorityVoteMulti  takes the weight tensors and every worker's gradient tensors where they are (a table
+                         of device addresses, built once) and runs the fused step over the concatenated index
+                         space with per-tensor ragged ends: no copy at all.
 
 Only memory plumbing lives here; all arithmetic is in libsignvote.
 """
@@ -81,3 +86,35 @@ class SignumMajorityVote:
         if self.v is not None:
             self.v.copy_(state["v"])
         self.steps = int(state["steps"])
+
+
+class SignumMajorityVoteMulti:
+    """Signum with majority vote (Algorithm 1) on tensors that stay where they are.
+
+    params          list of T weight tensors on the GPU (updated in place)
+    worker_grads    M lists of T gradient tensors (worker m's gradient of tensor t); the same tensor objects
+                    must be refilled in place every step (their addresses are in the plan)
+    Momenta (fp32) are allocated here, one 128-byte aligned slice per tensor in one buffer per worker.
+    step()          one fused launch over all tensors
+    """
+
+    def __init__(self, params, worker_grads, lr=1e-4, beta=0.9, weight_decay=0.0):
+        self.params = list(params)
+        self.worker_grads = [list(row) for row in worker_grads]
+        self.M = len(self.worker_grads)
+        self.lr, self.beta, self.weight_decay = float(lr), float(beta), float(weight_decay)
+        self.momenta = None
+        if self.beta > 0:
+            offs, off = [], 0
+            for p in self.params:
+                offs.append(off)
+                off += ((p.numel() + 31) // 32) * 32
+            dev = self.params[0].device
+            self._vbuf = torch.zeros((self.M, max(off, 32)), dtype=torch.float32, device=dev)
+            self.momenta = [[self._vbuf[m, o:o + p.numel()] for o, p in zip(offs, self.params)] for m in range(self.M)]
+        self.plan = _b.MultiTensorPlan(self.params, self.worker_grads, self.momenta)
+        self.steps = 0
+
+    def step(self):
+        _b.signum_step_multi(self.plan, self.beta, self.lr, self.weight_decay)
+        self.steps += 1

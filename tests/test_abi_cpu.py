@@ -30,7 +30,8 @@ def _declared_symbols():
 def test_header_symbols_are_exported(lib):
     names = _declared_symbols()
     assert {"ssv_sign_pack", "ssv_signum_momentum_pack", "ssv_majority_vote", "ssv_apply_sign_update",
-            "ssv_vote_apply", "ssv_signum_step", "ssv_status_string", "ssv_version", "ssv_bench_copy"} <= set(names)
+            "ssv_vote_apply", "ssv_signum_step", "ssv_status_string", "ssv_version", "ssv_bench_copy",
+            "ssv_multi_plan_bytes", "ssv_multi_plan_fill", "ssv_signum_step_multi"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in signvote.h but not exported"
 
@@ -82,6 +83,66 @@ def test_argument_validation_needs_no_device(lib):
     assert lib.ssv_bench_copy(None, P, 1024, None) == -1
     assert lib.ssv_bench_copy(P, P + 4096, 1000, None) == -2
     assert lib.ssv_bench_copy(P + 8, P + 4096, 1024, None) == -3
+
+
+def test_multi_tensor_plan_is_built_on_the_host(lib):
+    # the plan is sized and filled without touching a device: fake (aligned) device addresses suffice
+    import numpy as np
+    lib.ssv_multi_plan_bytes.restype = ctypes.c_size_t
+    T, M = 5, 3
+    n_list = [1, 63, 4096, 4097, 10_000]                    # 1 + 1 + 1 + 2 + 3 = 8 units of 4096 coordinates
+    n = (ctypes.c_int64 * T)(*n_list)
+    nbytes = lib.ssv_multi_plan_bytes(T, M, n)
+    assert nbytes > 0 and nbytes % 8 == 0
+    assert lib.ssv_multi_plan_bytes(0, M, n) == 0 and lib.ssv_multi_plan_bytes(T, 0, n) == 0
+    assert lib.ssv_multi_plan_bytes(T, 1024, n) == 0 and lib.ssv_multi_plan_bytes(T, M, None) == 0
+    bad = (ctypes.c_int64 * T)(1, 0, 5, 5, 5)
+    assert lib.ssv_multi_plan_bytes(T, M, bad) == 0
+    huge = (ctypes.c_int64 * 2)(1 << 40, 1)                  # sum beyond the coordinate limit
+    assert lib.ssv_multi_plan_bytes(2, M, huge) == 0
+    # more tensors, more workers or more units need more bytes
+    assert lib.ssv_multi_plan_bytes(T, M + 1, n) > nbytes
+    n2 = (ctypes.c_int64 * T)(1, 63, 4096, 4097, 10_000 + 400_000)
+    assert lib.ssv_multi_plan_bytes(T, M, n2) > nbytes
+
+    xs = (ctypes.c_void_p * T)(*[0x10000 * (t + 1) for t in range(T)])
+    gs = (ctypes.c_void_p * (T * M))(*[0x1000000 + 0x10000 * k for k in range(T * M)])
+    vs = (ctypes.c_void_p * (T * M))(*[0x9000000 + 0x10000 * k for k in range(T * M)])
+    buf = np.zeros(nbytes // 8 + 1, np.int64)
+    host = buf.ctypes.data
+    fill = lib.ssv_multi_plan_fill
+    assert fill(host, nbytes, T, M, n, xs, 0, gs, 0, vs) == 0
+    words = buf.view(np.uint64)
+    assert bytes(words[:1].tobytes()) == b"SSVPLAN1"
+    assert int(words[1]) == nbytes and [int(w) for w in words[2:6]] == [T, M, 8, sum(n_list)]
+    assert buf[nbytes // 8] == 0                                              # nothing written past the stated size
+    # argument errors
+    assert fill(None, nbytes, T, M, n, xs, 0, gs, 0, vs) == -1
+    assert fill(host, nbytes, T, M, n, None, 0, gs, 0, vs) == -1
+    assert fill(host, nbytes, T, M, n, xs, 0, None, 0, vs) == -1
+    assert fill(host, nbytes - 8, T, M, n, xs, 0, gs, 0, vs) == -2
+    assert fill(host, nbytes, T, M, bad, xs, 0, gs, 0, vs) == -2
+    assert fill(host, nbytes, T, M, n, xs, 2, gs, 0, vs) == -4
+    assert fill(host, nbytes, T, M, n, xs, 0, gs, 7, vs) == -4
+    assert fill(host + 4, nbytes, T, M, n, xs, 0, gs, 0, vs) == -3
+    gs_bad = (ctypes.c_void_p * (T * M))(*[0x1000000 + 0x10000 * k + (2 if k == 7 else 0) for k in range(T * M)])
+    assert fill(host, nbytes, T, M, n, xs, 0, gs_bad, 0, vs) == -3           # fp32 gradient at an odd half-word
+    assert fill(host, nbytes, T, M, n, xs, 0, gs_bad, 1, vs) == 0            # fine for bf16
+    gs_null = (ctypes.c_void_p * (T * M))(*[0x1000000 + 0x10000 * k if k != 4 else 0 for k in range(T * M)])
+    assert fill(host, nbytes, T, M, n, xs, 0, gs_null, 0, vs) == -1
+    # the step validates its arguments before any launch
+    step = lib.ssv_signum_step_multi
+    step.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_void_p]
+    assert fill(host, nbytes, T, M, n, xs, 0, gs, 0, vs) == 0
+    assert step(None, 0x1000, 0.9, 1e-3, 0.0, None) == -1
+    assert step(host, None, 0.9, 1e-3, 0.0, None) == -1
+    assert step(host, 0x1004, 0.9, 1e-3, 0.0, None) == -3
+    assert step(host, 0x1000, 1.0, 1e-3, 0.0, None) == -5
+    assert step(host, 0x1000, 0.9, float("inf"), 0.0, None) == -5
+    junk = np.zeros(64, np.int64)
+    assert step(junk.ctypes.data, 0x1000, 0.9, 1e-3, 0.0, None) == -2         # not a plan
+    assert fill(host, nbytes, T, M, n, xs, 0, gs, 0, None) == 0               # signSGD plan: no momentum
+    assert step(host, 0x1000, 0.9, 1e-3, 0.0, None) == -5                     # momentum asked without v
 
 
 def test_binding_refuses_cpu_tensors():

@@ -226,3 +226,46 @@ def test_small_model_trains_through_the_flat_layout(sv):
     opt.load_state_dict(state)
     opt.step()
     assert torch.equal(opt.x, after)
+
+
+def test_small_model_trains_with_gradients_left_where_autograd_put_them(sv):
+    # the same two-layer network, but every worker's gradients stay in the tensors autograd wrote them to; the
+    # multi-tensor step takes them from there (no copy into a flat buffer), one launch per step
+    torch.manual_seed(0)
+    M, steps = 5, 60
+    shapes = [(64, 20), (64,), (1, 64), (1,)]
+    stds = (0.2, 0.0, 0.1, 0.0)
+    params = [(torch.randn(s, device=DEV) * std).requires_grad_() for s, std in zip(shapes, stds)]
+    worker_grads = [[torch.zeros(s, device=DEV) for s in shapes] for _ in range(M)]
+    opt = sv.SignumMajorityVoteMulti([p.detach() for p in params], worker_grads, lr=2e-3, beta=0.9)
+    w_true = torch.randn(20, device=DEV)
+
+    def batch(seed, n=64):
+        gen = torch.Generator(device=DEV).manual_seed(seed)
+        xb = torch.randn(n, 20, device=DEV, generator=gen)
+        yb = torch.tanh(xb @ w_true)[:, None] + 0.05 * torch.randn(n, 1, device=DEV, generator=gen)
+        return xb, yb
+
+    def loss_fn(xb, yb):
+        h = torch.relu(xb @ params[0].T + params[1])
+        return ((h @ params[2].T + params[3] - yb) ** 2).mean()
+
+    x_ref = [_host(p.detach()).reshape(-1).copy() for p in params]
+    v_ref = [np.zeros((M, p.numel()), np.float32) for p in params]
+    xe, ye = batch(10_000, 2048)
+    first = loss_fn(xe, ye).item()
+    for k in range(steps):
+        for m in range(M):
+            for t, p in enumerate(params):
+                p.grad = worker_grads[m][t]                         # autograd accumulates into the worker's own tensors
+                p.grad.zero_()
+            loss_fn(*batch(1 + k * M + m)).backward()
+        opt.step()
+        torch.cuda.synchronize()
+        for t, p in enumerate(params):
+            g_h = np.stack([_host(worker_grads[m][t]).reshape(-1) for m in range(M)])
+            ora.signum_step(g_h, v_ref[t], 0.9, x_ref[t], 2e-3)
+            assert np.array_equal(_host(p.detach()).reshape(-1), x_ref[t]), f"tensor {t}, step {k}"
+    last = loss_fn(xe, ye).item()
+    print(f"small model, multi-tensor step: evaluation loss {first:.4f} -> {last:.4f} in {steps} fused steps", flush=True)
+    assert last < 0.5 * first

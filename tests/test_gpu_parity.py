@@ -463,6 +463,111 @@ def test_denormal_momentum_is_not_flushed(sv, g_kind):
     assert negative_denormals > 1000
 
 
+# ------------------------------------------------------------------ multi-tensor step (pointer table)
+
+def _ragged_sizes(rng, T):
+    """Tensor sizes like a model's: biases below a wavefront, odd lengths, exact multiples of the 4096-coordinate
+    unit and of the 256-coordinate tile, and a few large tensors that span many units."""
+    fixed = [1, 2, 3, 5, 17, 63, 64, 65, 255, 256, 257, 1000, 4095, 4096, 4097, 8192, 12_289, 65_536, 100_003, 262_147]
+    sizes = fixed + [int(rng.integers(1, 3000)) for _ in range(T - len(fixed))]
+    rng.shuffle(sizes)
+    return sizes
+
+
+@pytest.mark.parametrize("g_dtype,x_dtype,momentum", [(torch.float32, torch.float32, True),
+                                                      (torch.bfloat16, torch.bfloat16, True),
+                                                      (torch.float32, torch.bfloat16, False),
+                                                      (torch.bfloat16, torch.float32, True)])
+def test_step_multi_tensor_ragged(sv, g_dtype, x_dtype, momentum):
+    # 60 tensors of ragged sizes, every worker's gradient / momentum of every tensor an allocation of its own;
+    # every fifth tensor sits at an odd element offset (no vector alignment: the one-element-per-lane path).
+    # ONE launch per step; the oracle runs Algorithm 1 tensor by tensor.
+    M, T, steps = 7, 60, 3
+    beta = 0.9 if momentum else 0.0
+    lr, wd = (1e-4, 0.0) if x_dtype == torch.float32 else (1e-5, 0.0)
+    rng = np.random.default_rng(60)
+    sizes = _ragged_sizes(rng, T)
+    _log(f"multi-tensor step g={g_dtype} x={x_dtype} momentum={momentum}: {T} tensors, {sum(sizes)} coordinates")
+
+    def alloc(n, dtype, t, fill):
+        off = 1 if t % 5 == 4 else 0                          # misaligned view for every fifth tensor
+        buf = torch.full((n + 9,), fill, dtype=dtype, device=DEV)
+        return buf, buf[off:off + n]
+
+    xbufs, params = zip(*[alloc(n, x_dtype, t, 7.0) for t, n in enumerate(sizes)])
+    for t, p in enumerate(params):
+        p.copy_(wl.gaussian((sizes[t],), 0.02, seed=100 + t, device=DEV))
+    gbufs, grads, vbufs, moms = [], [], [], []
+    for m in range(M):
+        b, g = zip(*[alloc(n, g_dtype, t, 3.0) for t, n in enumerate(sizes)])
+        gbufs.append(b), grads.append(list(g))
+        if momentum:
+            b, v = zip(*[alloc(n, torch.float32, t, 0.0) for t, n in enumerate(sizes)])
+            vbufs.append(b), moms.append(list(v))
+    plan = sv.MultiTensorPlan(list(params), grads, moms if momentum else None)
+    assert plan.numel == sum(sizes) and plan.T == T and plan.M == M
+    x_ref = [wl.to_numpy(p.contiguous()).copy() for p in params]
+    v_ref = [np.zeros((M, n), np.float32) for n in sizes] if momentum else [None] * T
+    mus = [wl.shared_mean(n, seed=500 + t, device=DEV) for t, n in enumerate(sizes)]
+    for step in range(steps):
+        for t, n in enumerate(sizes):
+            gt = wl.worker_gradients(mus[t], M, step, base_seed=9000 + 31 * t, dtype=g_dtype)
+            for m in range(M):
+                grads[m][t].copy_(gt[m])
+        sv.signum_step_multi(plan, beta, lr, wd)
+        torch.cuda.synchronize()
+        for t, n in enumerate(sizes):
+            g_h = np.stack([wl.to_numpy(grads[m][t].contiguous()) for m in range(M)])
+            ora.signum_step(g_h, v_ref[t], beta, x_ref[t], lr, wd)
+            assert np.array_equal(wl.to_numpy(params[t].contiguous()), x_ref[t]), f"weights of tensor {t} (n={n}), step {step}"
+            if momentum:
+                v_gpu = np.stack([wl.to_numpy(moms[m][t].contiguous()) for m in range(M)])
+                assert np.array_equal(v_gpu, v_ref[t]), f"momentum of tensor {t} (n={n}), step {step}"
+    # nothing outside the tensors was touched: guard elements keep their fill
+    for t, n in enumerate(sizes):
+        off = 1 if t % 5 == 4 else 0
+        assert (xbufs[t][:off] == 7.0).all() and (xbufs[t][off + n:] == 7.0).all(), f"wrote outside weights {t}"
+        for m in range(M):
+            assert (gbufs[m][t][off + n:] == 3.0).all()
+            if momentum:
+                assert (vbufs[m][t][:off] == 0.0).all() and (vbufs[m][t][off + n:] == 0.0).all(), f"outside momentum {t}"
+
+
+def test_step_multi_equals_flat_step_on_one_large_tensor(sv):
+    # a single tensor: the multi-tensor launch must equal the flat fused step bit for bit, ragged end included
+    M, d = 15, 300_007
+    mu = wl.shared_mean(d, seed=1, device=DEV)
+    g = wl.worker_gradients(mu, M, 0, base_seed=77)
+    x_flat = wl.gaussian((d,), 0.02, seed=2, device=DEV)
+    x_multi = x_flat.clone()
+    v_flat = torch.zeros((M, d), device=DEV)
+    v_rows = [torch.zeros((d,), device=DEV) for _ in range(M)]
+    plan = sv.MultiTensorPlan([x_multi], [[g[m].clone()] for m in range(M)], [[v_rows[m]] for m in range(M)])
+    for _ in range(3):
+        sv.signum_step(g, v_flat, 0.9, x_flat, 1e-4)
+        sv.signum_step_multi(plan, 0.9, 1e-4)
+    torch.cuda.synchronize()
+    assert torch.equal(x_flat, x_multi)
+    assert all(torch.equal(v_flat[m], v_rows[m]) for m in range(M))
+
+
+def test_multi_plan_rejects_bad_tensor_lists(sv):
+    x = [torch.zeros(10, device=DEV), torch.zeros(20, device=DEV)]
+    g = [[torch.zeros(10, device=DEV), torch.zeros(20, device=DEV)] for _ in range(3)]
+    with pytest.raises(ValueError):
+        sv.MultiTensorPlan(x, [row[:1] for row in g])                       # a worker misses a tensor
+    with pytest.raises(ValueError):
+        sv.MultiTensorPlan(x, [[torch.zeros(10, device=DEV), torch.zeros(21, device=DEV)]] * 3)   # size mismatch
+    with pytest.raises(ValueError):
+        sv.MultiTensorPlan(x, g, [[t.to(torch.bfloat16) for t in row] for row in g])                # momentum must be fp32
+    with pytest.raises(ValueError):
+        sv.MultiTensorPlan([torch.zeros(4, 4, device=DEV).T, x[1]], g)                             # not contiguous
+    plan = sv.MultiTensorPlan(x, g)                                                                   # signSGD plan
+    with pytest.raises(sv.SignvoteError) as e:
+        sv.signum_step_multi(plan, 0.9, 1e-3)                                                        # momentum without v
+    assert e.value.status == -5
+
+
 def test_argument_errors_leave_buffers_untouched(sv):
     lib = sv.load_library()
     d, M = 1000, 3
