@@ -1,4 +1,4 @@
-"""ctypes loader for the CPU oracle (oracle/signvote_oracle.c).
+"""ctypes loader for the CPU oracle (oracle/signvote_oracle.c, oracle/qsgd_oracle.c).
 
 TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and by the
 cpu_baseline leg of bench.py.  Nothing under paper_1810_05291_amd/ imports this, and
@@ -27,6 +27,7 @@ def lib():
         _lib = ctypes.CDLL(path)
         _lib.ora_version.restype = ctypes.c_int
         _lib.ora_max_threads.restype = ctypes.c_int
+        _lib.ora_qsgd_norm_f64.restype = ctypes.c_double
     return _lib
 
 
@@ -236,3 +237,101 @@ def signum_step(g2d, v2d, beta, x, lr, wd=0.0, want_signs=False, worker_flip=Non
                                _f(wd), _p(vote), _p(signs), _i64(words_for(d)), _p(flip))
     assert rc == 0, rc
     return vote, signs
+
+
+# ---- ternary QSGD (oracle/qsgd_oracle.c) -------------------------------------------------
+
+QSGD_L2 = 0
+QSGD_MAX = 1
+
+
+def qsgd_norm_f64(g, kind):
+    g = _chk(np.ascontiguousarray(g), np.float32)
+    return float(lib().ora_qsgd_norm_f64(_p(g), _i64(g.size), ctypes.c_int(kind)))
+
+
+def qsgd_quantize_row(g, u, norm):
+    """codes in {-1, 0, +1} (int8) for one gradient row, uniforms u in [0, 1), and the row's norm (fp32)."""
+    g, u = _chk(np.ascontiguousarray(g), np.float32), _chk(np.ascontiguousarray(u), np.float32)
+    assert g.shape == u.shape and g.ndim == 1
+    q = np.empty(g.size, np.int8)
+    lib().ora_qsgd_quantize_row(_p(g), _p(u), _i64(g.size), _f(norm), _p(q))
+    return q
+
+
+def qsgd_pack(q):
+    q = _chk(np.ascontiguousarray(q), np.int8)
+    nz, sg = np.empty(words_for(q.size), np.uint64), np.empty(words_for(q.size), np.uint64)
+    lib().ora_qsgd_pack(_p(q), _i64(q.size), _p(nz), _p(sg))
+    return nz, sg
+
+
+def qsgd_unpack(nz, sg, d):
+    nz, sg = _chk(np.ascontiguousarray(nz), np.uint64), _chk(np.ascontiguousarray(sg), np.uint64)
+    q = np.empty(int(d), np.int8)
+    lib().ora_qsgd_unpack(_p(nz), _p(sg), _i64(d), _p(q))
+    return q
+
+
+def qsgd_average(q2d, norms):
+    q2d, norms = _chk(np.ascontiguousarray(q2d), np.int8), _chk(np.ascontiguousarray(norms), np.float32)
+    M, d = q2d.shape
+    avg = np.empty(d, np.float32)
+    lib().ora_qsgd_average(_p(q2d), _p(norms), ctypes.c_int(M), _i64(d), _p(avg))
+    return avg
+
+
+def qsgd_average_f64(q2d, norms):
+    q2d, norms = _chk(np.ascontiguousarray(q2d), np.int8), _chk(np.ascontiguousarray(norms), np.float32)
+    M, d = q2d.shape
+    avg = np.empty(d, np.float64)
+    lib().ora_qsgd_average_f64(_p(q2d), _p(norms), ctypes.c_int(M), _i64(d), _p(avg))
+    return avg
+
+
+def qsgd_update(x, avg, lr):
+    """In place on x (fp32, or bf16 bit patterns as uint16)."""
+    _chk(avg, np.float32)
+    assert x.ndim == 1 and x.flags["C_CONTIGUOUS"] and x.size == avg.size
+    if x.dtype == np.float32:
+        lib().ora_qsgd_update_f32(_p(x), _p(avg), _i64(x.size), _f(lr))
+    else:
+        _chk(x, np.uint16)
+        lib().ora_qsgd_update_bf16(_p(x), _p(avg), _i64(x.size), _f(lr))
+    return x
+
+
+def qsgd_norms(g2d, kind):
+    M, d, gs = _rows(g2d)
+    norms = np.empty(M, np.float32)
+    rc = lib().ora_qsgd_norms(_p(g2d), ctypes.c_int(_dt_of(g2d)), ctypes.c_int(M), _i64(d), _i64(gs),
+                              ctypes.c_int(kind), _p(norms))
+    assert rc == 0
+    return norms
+
+
+def qsgd_quantize(g2d, u2d, norms):
+    """Packed (nonzero, sign) planes, each uint64 [M, ceil(d/64)]."""
+    M, d, gs = _rows(g2d)
+    Mu, du, us = _rows(u2d)
+    assert (M, d) == (Mu, du) and u2d.dtype == np.float32
+    norms = _chk(np.ascontiguousarray(norms), np.float32)
+    assert norms.size == M
+    nz, sg = np.zeros((M, words_for(d)), np.uint64), np.zeros((M, words_for(d)), np.uint64)
+    rc = lib().ora_qsgd_quantize(_p(g2d), ctypes.c_int(_dt_of(g2d)), _p(u2d), _p(norms), ctypes.c_int(M), _i64(d),
+                                 _i64(gs), _i64(us), _p(nz), _p(sg), _i64(words_for(d)))
+    assert rc == 0
+    return nz, sg
+
+
+def qsgd_aggregate_apply(nz2d, sg2d, norms, d, x=None, lr=0.0):
+    """Average of the decoded vectors (returned, fp32); if x is given it is updated in place."""
+    M, W, ss = _rows(nz2d)
+    M2, W2, ss2 = _rows(sg2d)
+    assert (M, W, ss) == (M2, W2, ss2) and W >= words_for(d)
+    norms = _chk(np.ascontiguousarray(norms), np.float32)
+    avg = np.empty(int(d), np.float32)
+    rc = lib().ora_qsgd_aggregate_apply(_p(nz2d), _p(sg2d), _p(norms), ctypes.c_int(M), _i64(d), _i64(ss), _p(avg),
+                                        _p(x), ctypes.c_int(_dt_of(x) if x is not None else F32), _f(lr))
+    assert rc == 0
+    return avg

@@ -3,15 +3,15 @@ import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "signvote_oracle.c")
+SRCS = [os.path.join(HERE, "signvote_oracle.c"), os.path.join(HERE, "qsgd_oracle.c")]
 LIB = os.path.join(HERE, "libsignvote_oracle.so")
 
 
 def build(force: bool = True) -> str:
-    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+    if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(src) for src in SRCS):
         return LIB
     cmd = ["gcc", "-std=c11", "-O2", "-fopenmp", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
-           "-Wall", "-Wextra", "-o", LIB, SRC, "-lm"]
+           "-Wall", "-Wextra", "-o", LIB, *SRCS, "-lm"]
     subprocess.run(cmd, check=True)
     return LIB
 
