@@ -131,7 +131,35 @@ def other_kernels(torch, sv, wl, dev, quick):
     ms = time_launches(torch, lambda i: sv.signum_step(gnat[i % 4], vnat, 0.9, x, 1e-4), n(50), warmup=3)
     out["signum_step_resnet50_M15_natural_stride"] = entry(ms, (12.0 * M + 8) * d, row_stride=d,
                                                            worker_coords_per_s=M * d / ms * 1e3)
-    del gnat, vnat, grads, v, mu
+    del gnat, vnat
+
+    # ---- the same step over the model's 161 separate parameter tensors (every worker's gradient and momentum of
+    # every tensor an allocation of its own, 15 x 161 x 2 of them): one launch through the pointer table
+    shapes = wl.resnet50_parameter_shapes()
+    sizes = [int(torch.Size(s).numel()) for s in shapes]
+    params = [torch.zeros(k, device=dev) for k in sizes]
+    mgrads = [[wl.gaussian((k,), 1e-2, seed=4000 + 200 * m + t, device=dev) for t, k in enumerate(sizes)] for m in range(M)]
+    mmoms = [[torch.zeros(k, device=dev) for k in sizes] for m in range(M)]
+    plan = sv.MultiTensorPlan(params, mgrads, mmoms)
+    ms = time_launches(torch, lambda i: sv.signum_step_multi(plan, 0.9, 1e-4), n(50), warmup=3)
+    out["signum_step_multi_resnet50_161_tensors_M15"] = entry(ms, (12.0 * M + 8) * d, tensors=len(sizes), launches=1,
+                                                               plan_bytes=plan.nbytes,
+                                                               worker_coords_per_s=M * d / ms * 1e3)
+    # what a caller without it pays first: copying every worker's 161 gradient tensors into the flat rows
+    flat = grads[0]
+
+    def gather(i):
+        for m in range(M):
+            off = 0
+            for t, k in enumerate(sizes):
+                flat[m, off:off + k].copy_(mgrads[m][t])
+                off += k
+
+    ms_copy = time_launches(torch, gather, max(2, n(5)), warmup=1)
+    out["gather_into_flat_rows_resnet50_M15"] = {"ms": ms_copy, "copies": M * len(sizes),
+                                                 "note": "torch copy_ of every gradient tensor into the flat [M][d] buffer: "
+                                                         "the per-step cost the multi-tensor entry point removes"}
+    del plan, params, mgrads, mmoms, flat, grads, v, mu
 
     # ---- server-side and update entry points, 8 rotating buffer sets (packed rows 8 x 48 MB, weights 8 x 102 MB)
     xs = [wl.gaussian((d,), 0.02, seed=20 + k, device=dev) for k in range(8)]

@@ -25,6 +25,7 @@ from .generators import (  # noqa: F401
     shared_mean,
     worker_gradients,
     random_words,
+    resnet50_parameter_shapes,
     bernoulli_packed_rows,
     special_values_f32,
     words_for,

@@ -59,6 +59,25 @@ def worker_gradients(mu, M: int, step: int, base_seed: int, noise_std: float = 1
     return rows
 
 
+def resnet50_parameter_shapes():
+    """Shapes of the 161 parameter tensors of the 50-layer residual network the paper trains on ImageNet
+    (bottleneck blocks [3, 4, 6, 3] of widths 64..512 with 4x expansion, batch-norm scale and shift after every
+    convolution, a 1000-way linear classifier): 25,557,032 parameters in tensors of 64 .. 2,359,296 elements."""
+    shapes = [(64, 3, 7, 7), (64,), (64,)]
+    inplanes = 64
+    for planes, blocks in ((64, 3), (128, 4), (256, 6), (512, 3)):
+        for b in range(blocks):
+            shapes += [(planes, inplanes, 1, 1), (planes,), (planes,),
+                       (planes, planes, 3, 3), (planes,), (planes,),
+                       (4 * planes, planes, 1, 1), (4 * planes,), (4 * planes,)]
+            if b == 0:                                   # projection shortcut of the first block of a stage
+                shapes += [(4 * planes, inplanes, 1, 1), (4 * planes,), (4 * planes,)]
+            inplanes = 4 * planes
+    shapes += [(1000, 2048), (1000,)]
+    assert sum(int(np.prod(s)) for s in shapes) == RESNET50_D and len(shapes) == 161
+    return shapes
+
+
 def random_words(shape, seed: int, device="cpu"):
     """Uniform random 64-bit patterns (int64 storage): fair, independent sign bits."""
     g = _gen(seed, device)
