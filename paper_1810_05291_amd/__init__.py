@@ -23,5 +23,11 @@ from .binding import (  # noqa: F401
     bench_copy,
     MultiTensorPlan,
     signum_step_multi,
+    SSV_QSGD_L2,
+    SSV_QSGD_MAX,
+    qsgd_workspace,
+    qsgd_norms,
+    qsgd_quantize,
+    qsgd_aggregate_apply,
 )
 from .optim import FlatLayout, SignumMajorityVote, SignumMajorityVoteMulti  # noqa: F401,E402

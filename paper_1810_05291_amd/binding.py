@@ -11,6 +11,8 @@ import torch
 
 SSV_F32 = 0
 SSV_BF16 = 1
+SSV_QSGD_L2 = 0
+SSV_QSGD_MAX = 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -60,6 +62,14 @@ def load_library():
         lib.ssv_multi_plan_fill.restype = _c_int
         lib.ssv_signum_step_multi.argtypes = [_c_p, _c_p, _c_f, _c_f, _c_f, _c_p]
         lib.ssv_signum_step_multi.restype = _c_int
+        lib.ssv_qsgd_workspace_bytes.argtypes = [_c_int]
+        lib.ssv_qsgd_workspace_bytes.restype = ctypes.c_size_t
+        lib.ssv_qsgd_norms.argtypes = [_c_p, _c_int, _c_int, _c_i64, _c_i64, _c_int, _c_p, _c_p, ctypes.c_size_t, _c_p]
+        lib.ssv_qsgd_norms.restype = _c_int
+        lib.ssv_qsgd_quantize.argtypes = [_c_p, _c_int, _c_p, _c_p, _c_int, _c_i64, _c_i64, _c_i64, _c_p, _c_p, _c_i64, _c_p]
+        lib.ssv_qsgd_quantize.restype = _c_int
+        lib.ssv_qsgd_aggregate_apply.argtypes = [_c_p, _c_p, _c_p, _c_int, _c_i64, _c_i64, _c_p, _c_p, _c_int, _c_f, _c_p]
+        lib.ssv_qsgd_aggregate_apply.restype = _c_int
         lib.ssv_status_string.argtypes = [_c_int]
         lib.ssv_status_string.restype = ctypes.c_char_p
         lib.ssv_version.argtypes = []
@@ -315,6 +325,86 @@ def signum_step_multi(plan, beta, lr, weight_decay=0.0):
     _check("ssv_signum_step_multi",
            load_library().ssv_signum_step_multi(plan.host.data_ptr(), plan.device.data_ptr(), float(beta), float(lr),
                                                 float(weight_decay), _stream(plan.dev)))
+
+
+# ---- ternary QSGD (include/signvote_qsgd.h) ----------------------------------------------------------------
+
+def _norms_vec(norms, M):
+    if norms.dtype != torch.float32 or _vec(norms).numel() != M:
+        raise ValueError(f"norms must be {M} contiguous fp32 values")
+    return norms
+
+
+def qsgd_workspace(M, device):
+    """Scratch space for qsgd_norms (per-workgroup partial results), as a float64 tensor."""
+    nbytes = load_library().ssv_qsgd_workspace_bytes(int(M))
+    if nbytes == 0:
+        raise ValueError("M out of range")
+    return torch.empty((nbytes // 8,), dtype=torch.float64, device=device)
+
+
+def qsgd_norms(g, kind, norms=None, workspace=None):
+    """norms[m] = Euclidean norm (SSV_QSGD_L2) or largest magnitude (SSV_QSGD_MAX) of row m of g."""
+    M, d, gs = _rows(g)
+    if norms is not None:
+        _norms_vec(norms, M)
+    dev = _dev(g, norms, workspace)
+    if norms is None:
+        norms = torch.empty((M,), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = qsgd_workspace(M, dev)
+    if not workspace.is_contiguous():
+        raise ValueError("workspace must be contiguous")
+    _check("ssv_qsgd_norms",
+           load_library().ssv_qsgd_norms(_ptr(g), _dt(g), M, d, gs, int(kind), _ptr(norms), _ptr(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream(dev)))
+    return norms
+
+
+def qsgd_quantize(g, u, norms, nonzero=None, sign=None):
+    """Packed (nonzero, sign) planes of the ternary quantiser: keep coordinate i of row m iff u * norms[m] < |g|."""
+    M, d, gs = _rows(g)
+    Mu, du, us = _rows(u)
+    if (Mu, du) != (M, d) or u.dtype != torch.float32:
+        raise ValueError("u must be fp32 with the shape of g")
+    _norms_vec(norms, M)
+    ss = None
+    if (nonzero is None) != (sign is None):
+        raise ValueError("give both planes or neither")
+    if nonzero is not None:
+        ss = _packed_rows(nonzero, M, d, "nonzero")
+        if _packed_rows(sign, M, d, "sign") != ss:
+            raise ValueError("the two planes must have the same row stride")
+    dev = _dev(g, u, norms, nonzero, sign)
+    if nonzero is None:
+        nonzero = torch.empty((M, words_for(d)), dtype=torch.int64, device=dev)
+        sign = torch.empty((M, words_for(d)), dtype=torch.int64, device=dev)
+        ss = words_for(d)
+    _check("ssv_qsgd_quantize",
+           load_library().ssv_qsgd_quantize(_ptr(g), _dt(g), _ptr(u), _ptr(norms), M, d, gs, us, _ptr(nonzero),
+                                            _ptr(sign), ss, _stream(dev)))
+    return nonzero, sign
+
+
+def qsgd_aggregate_apply(nonzero, sign, norms, d, avg_out=None, x=None, lr=0.0):
+    """a = average over the workers of norms[m] * q_m; avg_out <- a and / or x <- x - lr a."""
+    d = _dim(d)
+    M = nonzero.shape[0] if nonzero.dim() == 2 else 0
+    ss = _packed_rows(nonzero, M, d, "nonzero")
+    if _packed_rows(sign, M, d, "sign") != ss:
+        raise ValueError("the two planes must have the same row stride")
+    _norms_vec(norms, M)
+    if avg_out is None and x is None:
+        raise ValueError("give avg_out, x or both")
+    if avg_out is not None and (avg_out.dtype != torch.float32 or _vec(avg_out).numel() != d):
+        raise ValueError(f"avg_out must be {d} contiguous fp32 values")
+    if x is not None:
+        _weights(x, d)
+    dev = _dev(nonzero, sign, norms, avg_out, x)
+    _check("ssv_qsgd_aggregate_apply",
+           load_library().ssv_qsgd_aggregate_apply(_ptr(nonzero), _ptr(sign), _ptr(norms), M, d, ss, _ptr(avg_out),
+                                                   _ptr(x), _dt(x) if x is not None else SSV_F32, float(lr), _stream(dev)))
+    return avg_out if avg_out is not None else x
 
 
 def bench_copy(src, dst):

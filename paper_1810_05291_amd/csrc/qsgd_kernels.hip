@@ -1,0 +1,341 @@
+// Ternary QSGD (the comparison compressors of Appendix B): per-row norms, the stochastic ternary choice packed
+// into two bit planes, and the 1-way average fused with the SGD update.  C ABI in include/signvote_qsgd.h.
+//
+// All three kernels are HBM-bound streams:
+//   norms      4 B read per worker-coordinate (2 for bf16); per-lane double accumulators, a fixed reduction
+//              order (lane -> wavefront -> workgroup -> one partial per workgroup in the workspace -> a finishing
+//              kernel that adds the partials of a row in index order), so results do not vary from run to run
+//   quantize   8 B read (g and u) and 2 bits written per worker-coordinate; packing as for the sign vectors
+//   aggregate  2 M bits read and 4 / 8 / 12 B moved per coordinate (avg_out and / or x)
+#include <cmath>
+
+#include "../../include/signvote.h"
+#include "../../include/signvote_qsgd.h"
+#include "device_utils.h"
+
+namespace ssv {
+
+constexpr int kNormParts = 256;          // workgroups (= partial results) per row in the norm kernel
+constexpr int kNormUnroll = 4;           // independent 16-byte loads per lane per round
+
+struct NormArgs {
+    const void* g;
+    double* partial;        // [M][kNormParts]
+    float* norms;           // [M]
+    int64_t d, g_stride;
+    int M, kind;
+};
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+__device__ __forceinline__ double wave_max(double v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = fmax(v, __shfl_xor(v, off, kWave));
+    return v;
+}
+
+// Workgroup (p, m) walks row m in rounds of kNormParts * 256 * VEC * kNormUnroll coordinates.
+template <typename GT, int VEC, bool L2>
+__global__ __launch_bounds__(kBlock) void qsgd_norm_partial_kernel(NormArgs a) {
+    __shared__ double wave_part[kWavesPerBlock];
+    const int m = blockIdx.y;
+    const GT* __restrict__ row = static_cast<const GT*>(a.g) + (int64_t)m * a.g_stride;
+    constexpr int64_t kChunk = (int64_t)kBlock * VEC;                       // coordinates per workgroup access
+    const int64_t round = (int64_t)kNormParts * kChunk * kNormUnroll;
+    double acc = 0.0;
+    for (int64_t base = (int64_t)blockIdx.x * kChunk * kNormUnroll; base < a.d; base += round) {
+        float gv[kNormUnroll][VEC];
+#pragma unroll
+        for (int k = 0; k < kNormUnroll; ++k) {
+            const int64_t j = base + k * kChunk + (int64_t)threadIdx.x * VEC;
+            const int64_t left = a.d - j;
+            const int n = left >= VEC ? VEC : (left > 0 ? (int)left : 0);
+            if (n > 0) {
+                load_vals_guarded<GT, VEC>(row + j, n, gv[k]);              // elements past the end read as 0
+            } else {
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) gv[k][c] = 0.0f;
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < kNormUnroll; ++k)
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) {
+                const double x = (double)gv[k][c];
+                if constexpr (L2) acc += x * x;                             // the square of an fp32 number is exact in double
+                else acc = fmax(acc, fabs(x));                              // fmax returns the number when one side is NaN
+            }
+    }
+    acc = L2 ? wave_sum(acc) : wave_max(acc);
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    if (lane == 0) wave_part[wave] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double r = wave_part[0];
+#pragma unroll
+        for (int w = 1; w < kWavesPerBlock; ++w) r = L2 ? r + wave_part[w] : fmax(r, wave_part[w]);
+        a.partial[(int64_t)m * kNormParts + blockIdx.x] = r;
+    }
+}
+
+// One workgroup per row: thread p holds partial p.
+template <bool L2>
+__global__ __launch_bounds__(kBlock) void qsgd_norm_finish_kernel(NormArgs a) {
+    static_assert(kNormParts == kBlock, "one partial per thread");
+    __shared__ double wave_part[kWavesPerBlock];
+    const int m = blockIdx.x;
+    double v = a.partial[(int64_t)m * kNormParts + threadIdx.x];
+    v = L2 ? wave_sum(v) : wave_max(v);
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    if (lane == 0) wave_part[wave] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double r = wave_part[0];
+#pragma unroll
+        for (int w = 1; w < kWavesPerBlock; ++w) r = L2 ? r + wave_part[w] : fmax(r, wave_part[w]);
+        a.norms[m] = (float)(L2 ? sqrt(r) : r);
+    }
+}
+
+// ---- quantise ---------------------------------------------------------------------------------------------
+struct QuantArgs {
+    const void* g;
+    const float* u;
+    const float* norms;
+    uint64_t* nonzero;
+    uint64_t* sign;
+    int64_t d, g_stride, u_stride, words_stride, W;
+};
+
+template <typename GT, int VEC, bool GUARD>
+__device__ __forceinline__ void quant_tile(const QuantArgs& a, const GT* __restrict__ grow, const float* __restrict__ urow,
+                                           float norm, uint64_t* nzrow, uint64_t* sgrow, int64_t tile, int lane) {
+    const int64_t j0 = tile * (int64_t)(kWave * VEC) + (int64_t)lane * VEC;
+    int n = VEC;
+    if constexpr (GUARD) {
+        const int64_t left = a.d - j0;
+        n = left >= VEC ? VEC : (left > 0 ? (int)left : 0);
+    }
+    float gv[VEC], uv[VEC];
+    if constexpr (GUARD) {
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) { gv[c] = 0.0f; uv[c] = 0.0f; }
+        if (n > 0) {
+            load_vals_guarded<GT, VEC>(grow + j0, n, gv);
+            load_vals_guarded<float, VEC>(urow + j0, n, uv);
+        }
+    } else {
+        load_vals<VEC>(grow + j0, gv);
+        load_vals<VEC>(urow + j0, uv);
+    }
+    uint32_t nzb[VEC], sgb[VEC];
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {
+        const float threshold = uv[c] * norm;
+        const bool keep = (threshold < fabsf(gv[c])) && (!GUARD || c < n);
+        nzb[c] = keep ? 1u : 0u;
+        sgb[c] = (keep && gv[c] > 0.0f) ? 1u : 0u;
+    }
+    // every lane of the wave reaches both calls (cross-lane merge of the 4-bit groups)
+    pack_store_tile<VEC>(nzrow, tile, a.W, lane, nzb);
+    pack_store_tile<VEC>(sgrow, tile, a.W, lane, sgb);
+}
+
+// Workgroup (b, m): 16 consecutive tiles of row m, wave w holding tiles w, w+4, w+8, w+12 (as in the fused step);
+// the ragged last workgroup of a row walks its tiles with bounds checks.
+template <typename GT, int VEC>
+__global__ __launch_bounds__(kBlock) void qsgd_quantize_kernel(QuantArgs a, int64_t nfull, int64_t ntiles) {
+    constexpr int SUB = 4;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int m = blockIdx.y;
+    const GT* __restrict__ grow = static_cast<const GT*>(a.g) + (int64_t)m * a.g_stride;
+    const float* __restrict__ urow = a.u + (int64_t)m * a.u_stride;
+    uint64_t* nzrow = a.nonzero + (int64_t)m * a.words_stride;
+    uint64_t* sgrow = a.sign + (int64_t)m * a.words_stride;
+    const float norm = a.norms[m];
+    const int64_t tile0 = (int64_t)blockIdx.x * (kWavesPerBlock * SUB) + wave;
+    if ((int64_t)blockIdx.x < nfull) {
+#pragma unroll
+        for (int s = 0; s < SUB; ++s)
+            quant_tile<GT, VEC, false>(a, grow, urow, norm, nzrow, sgrow, tile0 + s * kWavesPerBlock, lane);
+    } else {
+        for (int s = 0; s < SUB; ++s) {
+            const int64_t tile = tile0 + s * kWavesPerBlock;
+            if (tile < ntiles) quant_tile<GT, VEC, true>(a, grow, urow, norm, nzrow, sgrow, tile, lane);   // wave-uniform
+        }
+    }
+}
+
+// ---- 1-way average + update -------------------------------------------------------------------------------
+struct AggArgs {
+    const uint64_t* nonzero;
+    const uint64_t* sign;
+    const float* norms;
+    float* avg_out;
+    void* x;
+    int64_t d, words_stride;
+    int M;
+    float inv_m, lr;
+};
+
+// A lane owns VEC consecutive coordinates (VEC = 4, or 1 for unaligned outputs) and reads, for every worker, the
+// byte of each plane that holds their bits.
+template <typename XT, int VEC>
+__global__ __launch_bounds__(kBlock) void qsgd_aggregate_kernel(AggArgs a) {
+    const int64_t j0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * VEC;
+    if (j0 >= a.d) return;
+    const int64_t left = a.d - j0;
+    const int n = left >= VEC ? VEC : (int)left;
+    const uint8_t* __restrict__ nzb = reinterpret_cast<const uint8_t*>(a.nonzero) + (j0 >> 3);
+    const uint8_t* __restrict__ sgb = reinterpret_cast<const uint8_t*>(a.sign) + (j0 >> 3);
+    const int64_t row_bytes = a.words_stride * 8;
+    const int sh = (int)(j0 & 7);
+    float acc[VEC];
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) acc[c] = 0.0f;
+    constexpr int UM = 8;                                   // workers whose plane bytes are in flight together
+    for (int m0 = 0; m0 < a.M; m0 += UM) {
+        uint32_t nz[UM], sg[UM];
+#pragma unroll
+        for (int k = 0; k < UM; ++k) {
+            const bool on = m0 + k < a.M;
+            nz[k] = on ? (uint32_t)nzb[(int64_t)(m0 + k) * row_bytes] >> sh : 0u;
+            sg[k] = on ? (uint32_t)sgb[(int64_t)(m0 + k) * row_bytes] >> sh : 0u;
+        }
+#pragma unroll
+        for (int k = 0; k < UM; ++k) {                      // workers in index order: the fp32 sum has a fixed order
+            if (m0 + k < a.M) {
+                const float nm = a.norms[m0 + k];
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) {
+                    const bool keep = (nz[k] >> c) & 1u, pos = (sg[k] >> c) & 1u;
+                    if (keep) acc[c] = pos ? acc[c] + nm : acc[c] - nm;
+                }
+            }
+        }
+    }
+    float av[VEC];
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) av[c] = acc[c] * a.inv_m;
+    if (a.avg_out != nullptr) store_vals_guarded<float, VEC>(a.avg_out + j0, n, av);
+    if (a.x != nullptr) {
+        XT* xp = static_cast<XT*>(a.x) + j0;
+        float xv[VEC];
+        load_vals_guarded<XT, VEC>(xp, n, xv);
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) xv[c] = fmaf(-a.lr, av[c], xv[c]);
+        store_vals_guarded<XT, VEC>(xp, n, xv);
+    }
+}
+
+static inline bool aligned_to(const void* p, uintptr_t k) { return reinterpret_cast<uintptr_t>(p) % k == 0; }
+
+template <typename GT, int VEC>
+static hipError_t launch_norms(const NormArgs& a, hipStream_t s) {
+    (void)hipGetLastError();                 // a stale error of an earlier, unrelated call is not this launch's
+    if (a.kind == SSV_QSGD_L2) {
+        hipLaunchKernelGGL((qsgd_norm_partial_kernel<GT, VEC, true>), dim3(kNormParts, a.M), dim3(kBlock), 0, s, a);
+        hipLaunchKernelGGL((qsgd_norm_finish_kernel<true>), dim3(a.M), dim3(kBlock), 0, s, a);
+    } else {
+        hipLaunchKernelGGL((qsgd_norm_partial_kernel<GT, VEC, false>), dim3(kNormParts, a.M), dim3(kBlock), 0, s, a);
+        hipLaunchKernelGGL((qsgd_norm_finish_kernel<false>), dim3(a.M), dim3(kBlock), 0, s, a);
+    }
+    return hipGetLastError();
+}
+
+template <typename GT, int VEC>
+static hipError_t launch_quantize(const QuantArgs& a, int M, hipStream_t s) {
+    constexpr int64_t kTile = (int64_t)kWave * VEC;
+    constexpr int64_t kBlockTiles = kWavesPerBlock * 4;
+    const int64_t ntiles = (a.d + kTile - 1) / kTile;
+    const int64_t nfull = a.d / (kTile * kBlockTiles);
+    const int64_t grid = (ntiles + kBlockTiles - 1) / kBlockTiles;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL((qsgd_quantize_kernel<GT, VEC>), dim3((unsigned)grid, M), dim3(kBlock), 0, s, a, nfull, ntiles);
+    return hipGetLastError();
+}
+
+template <typename XT, int VEC>
+static hipError_t launch_aggregate(const AggArgs& a, hipStream_t s) {
+    const int64_t threads = (a.d + VEC - 1) / VEC;
+    const int64_t grid = (threads + kBlock - 1) / kBlock;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL((qsgd_aggregate_kernel<XT, VEC>), dim3((unsigned)grid), dim3(kBlock), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace ssv
+
+using namespace ssv;
+
+extern "C" {
+
+size_t ssv_qsgd_workspace_bytes(int M) {
+    if (M < 1 || M > SSV_MAX_WORKERS) return 0;
+    return (size_t)M * kNormParts * sizeof(double);
+}
+
+int ssv_qsgd_norms(const void* g, int g_dt, int M, int64_t d, int64_t g_row_stride, int kind, float* norms,
+                   void* workspace, size_t workspace_bytes, void* stream) {
+    if (g == nullptr || norms == nullptr || workspace == nullptr) return SSV_ERR_NULL;
+    if (g_dt != SSV_F32 && g_dt != SSV_BF16) return SSV_ERR_DTYPE;
+    if (M < 1 || M > SSV_MAX_WORKERS || d < 1 || d > SSV_MAX_COORDS || g_row_stride < d) return SSV_ERR_SHAPE;
+    if (kind != SSV_QSGD_L2 && kind != SSV_QSGD_MAX) return SSV_ERR_PARAM;
+    if (workspace_bytes < ssv_qsgd_workspace_bytes(M)) return SSV_ERR_SHAPE;
+    const uintptr_t es = g_dt == SSV_F32 ? 4 : 2;
+    if (!aligned_to(g, es) || !aligned_to(norms, 4) || !aligned_to(workspace, 8)) return SSV_ERR_ALIGN;
+    NormArgs a = {g, static_cast<double*>(workspace), norms, d, g_row_stride, M, kind};
+    const bool vec = aligned_to(g, 4 * es) && (M == 1 || g_row_stride % 4 == 0);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    if (g_dt == SSV_F32) e = vec ? launch_norms<float, 4>(a, s) : launch_norms<float, 1>(a, s);
+    else e = vec ? launch_norms<bf16, 4>(a, s) : launch_norms<bf16, 1>(a, s);
+    return e == hipSuccess ? SSV_OK : SSV_ERR_HIP;
+}
+
+int ssv_qsgd_quantize(const void* g, int g_dt, const float* u, const float* norms, int M, int64_t d,
+                      int64_t g_row_stride, int64_t u_row_stride, uint64_t* nonzero, uint64_t* sign,
+                      int64_t row_stride_words, void* stream) {
+    if (g == nullptr || u == nullptr || norms == nullptr || nonzero == nullptr || sign == nullptr) return SSV_ERR_NULL;
+    if (g_dt != SSV_F32 && g_dt != SSV_BF16) return SSV_ERR_DTYPE;
+    const int64_t W = (d + 63) / 64;
+    if (M < 1 || M > SSV_MAX_WORKERS || d < 1 || d > SSV_MAX_COORDS || g_row_stride < d || u_row_stride < d ||
+        row_stride_words < W)
+        return SSV_ERR_SHAPE;
+    const uintptr_t es = g_dt == SSV_F32 ? 4 : 2;
+    if (!aligned_to(g, es) || !aligned_to(u, 4) || !aligned_to(norms, 4) || !aligned_to(nonzero, 8) || !aligned_to(sign, 8))
+        return SSV_ERR_ALIGN;
+    QuantArgs a = {g, u, norms, nonzero, sign, d, g_row_stride, u_row_stride, row_stride_words, W};
+    const bool vec = aligned_to(g, 4 * es) && aligned_to(u, 16) && (M == 1 || (g_row_stride % 4 == 0 && u_row_stride % 4 == 0));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    if (g_dt == SSV_F32) e = vec ? launch_quantize<float, 4>(a, M, s) : launch_quantize<float, 1>(a, M, s);
+    else e = vec ? launch_quantize<bf16, 4>(a, M, s) : launch_quantize<bf16, 1>(a, M, s);
+    return e == hipSuccess ? SSV_OK : SSV_ERR_HIP;
+}
+
+int ssv_qsgd_aggregate_apply(const uint64_t* nonzero, const uint64_t* sign, const float* norms, int M, int64_t d,
+                             int64_t row_stride_words, float* avg_out, void* x, int x_dt, float lr, void* stream) {
+    if (nonzero == nullptr || sign == nullptr || norms == nullptr) return SSV_ERR_NULL;
+    if (avg_out == nullptr && x == nullptr) return SSV_ERR_NULL;
+    if (x != nullptr && x_dt != SSV_F32 && x_dt != SSV_BF16) return SSV_ERR_DTYPE;
+    if (M < 1 || M > SSV_MAX_WORKERS || d < 1 || d > SSV_MAX_COORDS || row_stride_words < (d + 63) / 64) return SSV_ERR_SHAPE;
+    if (x != nullptr && !std::isfinite(lr)) return SSV_ERR_PARAM;
+    const uintptr_t xes = x_dt == SSV_F32 ? 4 : 2;
+    if (!aligned_to(nonzero, 8) || !aligned_to(sign, 8) || !aligned_to(norms, 4) || !aligned_to(avg_out, 4)) return SSV_ERR_ALIGN;
+    if (x != nullptr && !aligned_to(x, xes)) return SSV_ERR_ALIGN;
+    AggArgs a = {nonzero, sign, norms, avg_out, x, d, row_stride_words, M, 1.0f / (float)M, lr};
+    const bool vec = aligned_to(avg_out, 16) && (x == nullptr || aligned_to(x, 4 * xes));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    if (x == nullptr || x_dt == SSV_F32) e = vec ? launch_aggregate<float, 4>(a, s) : launch_aggregate<float, 1>(a, s);
+    else e = vec ? launch_aggregate<bf16, 4>(a, s) : launch_aggregate<bf16, 1>(a, s);
+    return e == hipSuccess ? SSV_OK : SSV_ERR_HIP;
+}
+
+}  // extern "C"

@@ -7,7 +7,8 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADERS = [os.path.join(ROOT, "include", "signvote.h"), os.path.join(ROOT, "include", "signvote_bench.h")]
+HEADERS = [os.path.join(ROOT, "include", "signvote.h"), os.path.join(ROOT, "include", "signvote_bench.h"),
+           os.path.join(ROOT, "include", "signvote_qsgd.h")]
 
 
 @pytest.fixture(scope="module")
@@ -31,7 +32,8 @@ def test_header_symbols_are_exported(lib):
     names = _declared_symbols()
     assert {"ssv_sign_pack", "ssv_signum_momentum_pack", "ssv_majority_vote", "ssv_apply_sign_update",
             "ssv_vote_apply", "ssv_signum_step", "ssv_status_string", "ssv_version", "ssv_bench_copy",
-            "ssv_multi_plan_bytes", "ssv_multi_plan_fill", "ssv_signum_step_multi"} <= set(names)
+            "ssv_multi_plan_bytes", "ssv_multi_plan_fill", "ssv_signum_step_multi",
+            "ssv_qsgd_workspace_bytes", "ssv_qsgd_norms", "ssv_qsgd_quantize", "ssv_qsgd_aggregate_apply"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in signvote.h but not exported"
 
@@ -143,6 +145,47 @@ def test_multi_tensor_plan_is_built_on_the_host(lib):
     assert step(junk.ctypes.data, 0x1000, 0.9, 1e-3, 0.0, None) == -2         # not a plan
     assert fill(host, nbytes, T, M, n, xs, 0, gs, 0, None) == 0               # signSGD plan: no momentum
     assert step(host, 0x1000, 0.9, 1e-3, 0.0, None) == -5                     # momentum asked without v
+
+
+def test_qsgd_argument_validation_needs_no_device(lib):
+    P, W = 0x1000, 16
+    lib.ssv_qsgd_workspace_bytes.restype = ctypes.c_size_t
+    ws = lib.ssv_qsgd_workspace_bytes(3)
+    assert ws > 0 and lib.ssv_qsgd_workspace_bytes(0) == 0 and lib.ssv_qsgd_workspace_bytes(1024) == 0
+    assert lib.ssv_qsgd_workspace_bytes(6) == 2 * ws
+    norms = lib.ssv_qsgd_norms
+    norms.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
+                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    assert norms(None, 0, 3, 1000, 1000, 0, P, P, ws, None) == -1
+    assert norms(P, 0, 3, 1000, 1000, 0, None, P, ws, None) == -1
+    assert norms(P, 0, 3, 1000, 1000, 0, P, None, ws, None) == -1
+    assert norms(P, 0, 3, 1000, 1000, 0, P, P, ws - 8, None) == -2          # workspace too small
+    assert norms(P, 0, 3, 1000, 999, 0, P, P, ws, None) == -2
+    assert norms(P, 0, 0, 1000, 1000, 0, P, P, ws, None) == -2
+    assert norms(P, 3, 3, 1000, 1000, 0, P, P, ws, None) == -4
+    assert norms(P, 0, 3, 1000, 1000, 2, P, P, ws, None) == -5              # unknown norm
+    assert norms(P + 2, 0, 3, 1000, 1000, 0, P, P, ws, None) == -3
+    assert norms(P, 0, 3, 1000, 1000, 0, P, P + 4, ws, None) == -3
+    quant = lib.ssv_qsgd_quantize
+    quant.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
+                      ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+    assert quant(P, 0, None, P, 3, 1000, 1000, 1000, P, P, W, None) == -1
+    assert quant(P, 0, P, P, 3, 1000, 1000, 1000, P, None, W, None) == -1
+    assert quant(P, 0, P, P, 3, 1000, 1000, 999, P, P, W, None) == -2        # u rows shorter than d
+    assert quant(P, 0, P, P, 3, 1000, 1000, 1000, P, P, W - 1, None) == -2
+    assert quant(P, 5, P, P, 3, 1000, 1000, 1000, P, P, W, None) == -4
+    assert quant(P, 0, P + 2, P, 3, 1000, 1000, 1000, P, P, W, None) == -3
+    assert quant(P, 0, P, P, 3, 1000, 1000, 1000, P + 4, P, W, None) == -3
+    agg = lib.ssv_qsgd_aggregate_apply
+    agg.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
+                    ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_void_p]
+    assert agg(None, P, P, 3, 1000, W, P, P, 0, 0.1, None) == -1
+    assert agg(P, P, P, 3, 1000, W, None, None, 0, 0.1, None) == -1          # neither output
+    assert agg(P, P, P, 3, 1000, W - 1, P, P, 0, 0.1, None) == -2
+    assert agg(P, P, P, 3, 1000, W, P, P, 9, 0.1, None) == -4
+    assert agg(P, P, P, 3, 1000, W, P, P, 0, float("nan"), None) == -5
+    assert agg(P, P, P, 3, 1000, W, P + 2, P, 0, 0.1, None) == -3
+    assert agg(P, P, P, 3, 1000, W, P, P + 1, 1, 0.1, None) == -3
 
 
 def test_binding_refuses_cpu_tensors():
