@@ -50,6 +50,19 @@ int ssv_qsgd_norms(const void* g, int g_dt, int M, int64_t d, int64_t g_row_stri
                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * ssv_qsgd_norms for callers that cannot allocate device memory or bring a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  Same arguments, results and errors as
+ * ssv_qsgd_norms, but the partial results live in a fixed array inside the library (512 KiB per GPU, held until
+ * the process ends) instead of `workspace`; the call allocates and frees nothing.
+ *   Limit: M <= 256 rows, else SSV_ERR_SHAPE.
+ *   All calls on one GPU share that array: calls that overlap in time on one GPU (different streams or threads)
+ *   race and give wrong norms; calls on one stream, or otherwise ordered, are safe.
+ *   The array's device address is looked up on the first call on each GPU (SSV_ERR_HIP if that fails).
+ */
+int ssv_qsgd_norms_static(const void* g, int g_dt, int M, int64_t d, int64_t g_row_stride, int kind, float* norms,
+                          void* stream);
+
+/*
  * The ternary quantiser of Appendix B for every row: nonzero[m] / sign[m] bit i <- whether g[m][i] is kept / kept
  * and positive, with u[m][i] * norms[m] < |g[m][i]| as the keep rule.
  *   u          device, M rows of d fp32 uniforms in [0, 1), row stride u_row_stride

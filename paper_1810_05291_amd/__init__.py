@@ -27,6 +27,7 @@ from .binding import (  # noqa: F401
     SSV_QSGD_MAX,
     qsgd_workspace,
     qsgd_norms,
+    qsgd_norms_static,
     qsgd_quantize,
     qsgd_aggregate_apply,
 )

@@ -66,6 +66,8 @@ def load_library():
         lib.ssv_qsgd_workspace_bytes.restype = ctypes.c_size_t
         lib.ssv_qsgd_norms.argtypes = [_c_p, _c_int, _c_int, _c_i64, _c_i64, _c_int, _c_p, _c_p, ctypes.c_size_t, _c_p]
         lib.ssv_qsgd_norms.restype = _c_int
+        lib.ssv_qsgd_norms_static.argtypes = [_c_p, _c_int, _c_int, _c_i64, _c_i64, _c_int, _c_p, _c_p]
+        lib.ssv_qsgd_norms_static.restype = _c_int
         lib.ssv_qsgd_quantize.argtypes = [_c_p, _c_int, _c_p, _c_p, _c_int, _c_i64, _c_i64, _c_i64, _c_p, _c_p, _c_i64, _c_p]
         lib.ssv_qsgd_quantize.restype = _c_int
         lib.ssv_qsgd_aggregate_apply.argtypes = [_c_p, _c_p, _c_p, _c_int, _c_i64, _c_i64, _c_p, _c_p, _c_int, _c_f, _c_p]
@@ -358,6 +360,16 @@ def qsgd_norms(g, kind, norms=None, workspace=None):
     _check("ssv_qsgd_norms",
            load_library().ssv_qsgd_norms(_ptr(g), _dt(g), M, d, gs, int(kind), _ptr(norms), _ptr(workspace),
                                          workspace.numel() * workspace.element_size(), _stream(dev)))
+    return norms
+
+
+def qsgd_norms_static(g, kind, norms):
+    """qsgd_norms with the library's built-in scratch space (M <= 256): allocates nothing, so `norms` is required."""
+    M, d, gs = _rows(g)
+    _norms_vec(norms, M)
+    dev = _dev(g, norms)
+    _check("ssv_qsgd_norms_static",
+           load_library().ssv_qsgd_norms_static(_ptr(g), _dt(g), M, d, gs, int(kind), _ptr(norms), _stream(dev)))
     return norms
 
 

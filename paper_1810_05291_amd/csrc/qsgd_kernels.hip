@@ -8,6 +8,7 @@
 //   quantize   8 B read (g and u) and 2 bits written per worker-coordinate; packing as for the sign vectors
 //   aggregate  2 M bits read and 4 / 8 / 12 B moved per coordinate (avg_out and / or x)
 #include <cmath>
+#include <mutex>
 
 #include "../../include/signvote.h"
 #include "../../include/signvote_qsgd.h"
@@ -233,6 +234,34 @@ __global__ __launch_bounds__(kBlock) void qsgd_aggregate_kernel(AggArgs a) {
 
 static inline bool aligned_to(const void* p, uintptr_t k) { return reinterpret_cast<uintptr_t>(p) % k == 0; }
 
+// ---- scratch space inside the library, for callers that cannot allocate ----------------------------------------
+// The partial results of ssv_qsgd_norms_static live in this array instead of a caller's workspace: room for
+// kStaticMaxRows rows of kNormParts doubles (512 KiB).  Every GPU the library runs on holds its own copy at its
+// own address for the life of the process.  In host code the name `scratch` is only a handle for
+// hipGetSymbolAddress; kernels get the device address that call returns.
+constexpr int kStaticMaxRows = 256;
+static __device__ __align__(256) double scratch[(size_t)kStaticMaxRows * kNormParts];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static double* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device, looked up once per device.  nullptr on failure.
+static double* scratch_on_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = static_cast<double*>(p);
+    }
+    return g_scratch_ptr[dev];
+}
+
 template <typename GT, int VEC>
 static hipError_t launch_norms(const NormArgs& a, hipStream_t s) {
     (void)hipGetLastError();                 // a stale error of an earlier, unrelated call is not this launch's
@@ -296,6 +325,18 @@ int ssv_qsgd_norms(const void* g, int g_dt, int M, int64_t d, int64_t g_row_stri
     if (g_dt == SSV_F32) e = vec ? launch_norms<float, 4>(a, s) : launch_norms<float, 1>(a, s);
     else e = vec ? launch_norms<bf16, 4>(a, s) : launch_norms<bf16, 1>(a, s);
     return e == hipSuccess ? SSV_OK : SSV_ERR_HIP;
+}
+
+int ssv_qsgd_norms_static(const void* g, int g_dt, int M, int64_t d, int64_t g_row_stride, int kind, float* norms,
+                          void* stream) {
+    if (M > kStaticMaxRows) return SSV_ERR_SHAPE;          // the built-in scratch space holds 256 rows' partial results
+    if (g == nullptr || norms == nullptr) return SSV_ERR_NULL;
+    double* ws = scratch_on_current_device();
+    if (ws == nullptr) return SSV_ERR_HIP;
+    // Same validation and the same kernels as ssv_qsgd_norms.  Nothing needs clearing: every workgroup of the first
+    // kernel writes its partial result before the finishing kernel reads it, whatever the array held before.
+    return ssv_qsgd_norms(g, g_dt, M, d, g_row_stride, kind, norms, ws, sizeof(double) * (size_t)kStaticMaxRows * kNormParts,
+                          stream);
 }
 
 int ssv_qsgd_quantize(const void* g, int g_dt, const float* u, const float* norms, int M, int64_t d,
