@@ -159,7 +159,22 @@ def other_kernels(torch, sv, wl, dev, quick):
     out["gather_into_flat_rows_resnet50_M15"] = {"ms": ms_copy, "copies": M * len(sizes),
                                                  "note": "torch copy_ of every gradient tensor into the flat [M][d] buffer: "
                                                          "the per-step cost the multi-tensor entry point removes"}
-    del plan, params, mgrads, mmoms, flat, grads, v, mu
+    del plan, params, mgrads, mmoms, flat
+
+    # ---- the comparison compressors (ternary QSGD, Appendix B) on the same gradients: norms, quantise, average + update
+    u = torch.rand((M, stride), device=dev, generator=torch.Generator(device=dev).manual_seed(9))[:, :d]
+    norms = torch.empty((M,), device=dev)
+    ws = sv.qsgd_workspace(M, dev)
+    ms = time_launches(torch, lambda i: sv.qsgd_norms(grads[i % 4], sv.SSV_QSGD_L2, norms, ws), n(40))
+    out["qsgd_norms_l2_resnet50_M15"] = entry(ms, 4.0 * M * d, launches=2)
+    nzp = torch.empty((M, strideW), dtype=torch.int64, device=dev)[:, :W]
+    sgp = torch.empty((M, strideW), dtype=torch.int64, device=dev)[:, :W]
+    ms = time_launches(torch, lambda i: sv.qsgd_quantize(grads[i % 4], u, norms, nzp, sgp), n(40))
+    out["qsgd_quantize_resnet50_M15"] = entry(ms, (8 + 2 / 8) * M * d, bytes_per_worker_coordinate=8.25)
+    xq = [wl.gaussian((d,), 0.02, seed=60 + k, device=dev) for k in range(4)]
+    ms = time_launches(torch, lambda i: sv.qsgd_aggregate_apply(nzp, sgp, norms, d, x=xq[i % 4], lr=0.1), n(80), warmup=4)
+    out["qsgd_aggregate_apply_resnet50_M15"] = entry(ms, (2 * M / 8 + 8) * d, note="update only (no avg_out), 4 rotating weight sets")
+    del u, norms, ws, nzp, sgp, xq, grads, v, mu
 
     # ---- server-side and update entry points, 8 rotating buffer sets (packed rows 8 x 48 MB, weights 8 x 102 MB)
     xs = [wl.gaussian((d,), 0.02, seed=20 + k, device=dev) for k in range(8)]

@@ -6,7 +6,8 @@
 //              order (lane -> wavefront -> workgroup -> one partial per workgroup in the workspace -> a finishing
 //              kernel that adds the partials of a row in index order), so results do not vary from run to run
 //   quantize   8 B read (g and u) and 2 bits written per worker-coordinate; packing as for the sign vectors
-//   aggregate  2 M bits read and 4 / 8 / 12 B moved per coordinate (avg_out and / or x)
+//   aggregate  2 M bits read and 4 / 8 / 12 B moved per coordinate (avg_out and / or x); the per-lane sums are
+//              handed over through LDS so that the plane reads and the weight accesses are both contiguous
 #include <cmath>
 #include <mutex>
 
@@ -182,53 +183,81 @@ struct AggArgs {
     float inv_m, lr;
 };
 
-// A lane owns VEC consecutive coordinates (VEC = 4, or 1 for unaligned outputs) and reads, for every worker, the
-// byte of each plane that holds their bits.
+// A wavefront owns a tile of 2048 coordinates = 64 dwords of every plane row.  Lane l loads dword l of both planes
+// for every worker (two 256-byte reads per worker per wave) and sums the decoded values of ITS 32 coordinates in 32
+// registers, workers in index order.  The averages then change hands through LDS (a padded per-wave array, no bank
+// conflicts) so that the weight / average accesses are contiguous: lane l takes elements (i * 64 + l) * VEC of the
+// tile in access i.  A first version in which a lane read the plane BYTE of its 4 coordinates per worker was bound by
+// the number of load instructions (30 tiny loads per 4 coordinates at M = 15): 25% of the HBM peak.
 template <typename XT, int VEC>
-__global__ __launch_bounds__(kBlock) void qsgd_aggregate_kernel(AggArgs a) {
-    const int64_t j0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * VEC;
-    if (j0 >= a.d) return;
-    const int64_t left = a.d - j0;
-    const int n = left >= VEC ? VEC : (int)left;
-    const uint8_t* __restrict__ nzb = reinterpret_cast<const uint8_t*>(a.nonzero) + (j0 >> 3);
-    const uint8_t* __restrict__ sgb = reinterpret_cast<const uint8_t*>(a.sign) + (j0 >> 3);
-    const int64_t row_bytes = a.words_stride * 8;
-    const int sh = (int)(j0 & 7);
-    float acc[VEC];
+__global__ __launch_bounds__(kBlock) void qsgd_aggregate_kernel(AggArgs a, int64_t ntiles) {
+    constexpr int kTileCoords = kWave * 32;
+    constexpr int kPad = 33;                                        // row pitch of a lane's 32 values: odd => conflict-free
+    __shared__ float stage[kWavesPerBlock][kWave * kPad];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+    if (tile >= ntiles) return;                                     // wave-uniform; no workgroup barrier is used below
+    const int64_t W2 = 2 * ((a.d + 63) / 64);                       // dwords per plane row that exist
+    const int64_t dw = tile * kWave + lane;
+    const bool have = dw < W2;
+    const int64_t row_dw = 2 * a.words_stride;
+    const uint32_t* __restrict__ nzp = reinterpret_cast<const uint32_t*>(a.nonzero) + dw;
+    const uint32_t* __restrict__ sgp = reinterpret_cast<const uint32_t*>(a.sign) + dw;
+    float acc[32];
 #pragma unroll
-    for (int c = 0; c < VEC; ++c) acc[c] = 0.0f;
-    constexpr int UM = 8;                                   // workers whose plane bytes are in flight together
+    for (int c = 0; c < 32; ++c) acc[c] = 0.0f;
+    constexpr int UM = 4;                                           // workers whose plane dwords are in flight together
     for (int m0 = 0; m0 < a.M; m0 += UM) {
         uint32_t nz[UM], sg[UM];
 #pragma unroll
         for (int k = 0; k < UM; ++k) {
-            const bool on = m0 + k < a.M;
-            nz[k] = on ? (uint32_t)nzb[(int64_t)(m0 + k) * row_bytes] >> sh : 0u;
-            sg[k] = on ? (uint32_t)sgb[(int64_t)(m0 + k) * row_bytes] >> sh : 0u;
+            const bool on = have && m0 + k < a.M;
+            nz[k] = on ? stream_load(nzp + (int64_t)(m0 + k) * row_dw) : 0u;
+            sg[k] = on ? stream_load(sgp + (int64_t)(m0 + k) * row_dw) : 0u;
         }
 #pragma unroll
-        for (int k = 0; k < UM; ++k) {                      // workers in index order: the fp32 sum has a fixed order
+        for (int k = 0; k < UM; ++k) {                              // workers in index order: the fp32 sum has a fixed order
             if (m0 + k < a.M) {
                 const float nm = a.norms[m0 + k];
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) {
+                for (int c = 0; c < 32; ++c) {
                     const bool keep = (nz[k] >> c) & 1u, pos = (sg[k] >> c) & 1u;
-                    if (keep) acc[c] = pos ? acc[c] + nm : acc[c] - nm;
+                    acc[c] = keep ? (pos ? acc[c] + nm : acc[c] - nm) : acc[c];
                 }
             }
         }
     }
-    float av[VEC];
+    float* st = stage[wave];
 #pragma unroll
-    for (int c = 0; c < VEC; ++c) av[c] = acc[c] * a.inv_m;
-    if (a.avg_out != nullptr) store_vals_guarded<float, VEC>(a.avg_out + j0, n, av);
-    if (a.x != nullptr) {
-        XT* xp = static_cast<XT*>(a.x) + j0;
-        float xv[VEC];
-        load_vals_guarded<XT, VEC>(xp, n, xv);
+    for (int c = 0; c < 32; ++c) st[lane * kPad + c] = acc[c] * a.inv_m;       // coordinate 32 l + c of the tile
+    // the wave's own LDS writes are complete before its reads (same wave: only the counter wait is needed)
+    __builtin_amdgcn_s_waitcnt(0xc07f);                                          // lgkmcnt(0)
+    __builtin_amdgcn_wave_barrier();
+
+    const int64_t cbase = tile * (int64_t)kTileCoords;
+    const int64_t left = a.d - cbase;                                            // > 0
+    constexpr int kAcc = 32 / VEC;
+#pragma unroll 4
+    for (int i = 0; i < kAcc; ++i) {
+        const int off = (i * kWave + lane) * VEC;
+        const int64_t r = left - off;
+        const int n = r >= VEC ? VEC : (r > 0 ? (int)r : 0);
+        if (n == 0) continue;
+        float av[VEC];
 #pragma unroll
-        for (int c = 0; c < VEC; ++c) xv[c] = fmaf(-a.lr, av[c], xv[c]);
-        store_vals_guarded<XT, VEC>(xp, n, xv);
+        for (int c = 0; c < VEC; ++c) {
+            const int j = off + c;
+            av[c] = st[(j >> 5) * kPad + (j & 31)];
+        }
+        if (a.avg_out != nullptr) store_vals_guarded<float, VEC>(a.avg_out + cbase + off, n, av);
+        if (a.x != nullptr) {
+            XT* xp = static_cast<XT*>(a.x) + cbase + off;
+            float xv[VEC];
+            load_vals_guarded<XT, VEC>(xp, n, xv);
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) xv[c] = fmaf(-a.lr, av[c], xv[c]);
+            store_vals_guarded<XT, VEC>(xp, n, xv);
+        }
     }
 }
 
@@ -290,11 +319,11 @@ static hipError_t launch_quantize(const QuantArgs& a, int M, hipStream_t s) {
 
 template <typename XT, int VEC>
 static hipError_t launch_aggregate(const AggArgs& a, hipStream_t s) {
-    const int64_t threads = (a.d + VEC - 1) / VEC;
-    const int64_t grid = (threads + kBlock - 1) / kBlock;
+    const int64_t ntiles = (a.d + kWave * 32 - 1) / (kWave * 32);
+    const int64_t grid = (ntiles + kWavesPerBlock - 1) / kWavesPerBlock;
     if (grid > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     (void)hipGetLastError();
-    hipLaunchKernelGGL((qsgd_aggregate_kernel<XT, VEC>), dim3((unsigned)grid), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL((qsgd_aggregate_kernel<XT, VEC>), dim3((unsigned)grid), dim3(kBlock), 0, s, a, ntiles);
     return hipGetLastError();
 }
 

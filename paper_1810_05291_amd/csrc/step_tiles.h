@@ -27,9 +27,30 @@ struct TableRows {
     }
 };
 
-template <typename GT, int VEC, int SUB, bool MOM, bool OUT, bool GUARD, bool SERIAL, typename ROWS, int U>
-__device__ __forceinline__ void worker_group(const StepArgs& a, int m0, int64_t j0, const int (&nvalid)[SUB],
-                                             int lane, int64_t tile0, uint32_t (&cnt)[SUB][VEC]) {
+// Row starts of U consecutive workers.  Fetched one group ahead of their use, so that with TableRows the
+// pointer loads (scalar memory) overlap the previous group's row loads instead of lengthening a wave's chain
+// of dependent loads.
+template <typename GT, int U>
+struct RowStarts {
+    const GT* g[U];
+    float* v[U];
+};
+
+template <typename GT, bool MOM, typename ROWS, int U>
+__device__ __forceinline__ RowStarts<GT, U> fetch_rows(const StepArgs& a, int m0) {
+    RowStarts<GT, U> r;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        r.g[u] = ROWS::template g<GT>(a, m0 + u);
+        r.v[u] = MOM ? ROWS::v(a, m0 + u) : nullptr;
+    }
+    return r;
+}
+
+template <typename GT, int VEC, int SUB, bool MOM, bool OUT, bool GUARD, bool SERIAL, int U>
+__device__ __forceinline__ void worker_group(const StepArgs& a, const RowStarts<GT, U>& rows, int m0, int64_t j0,
+                                             const int (&nvalid)[SUB], int lane, int64_t tile0,
+                                             uint32_t (&cnt)[SUB][VEC]) {
     constexpr int64_t kTile = (int64_t)kWave * VEC * kWavesPerBlock;   // a wave's tiles are a block-row apart
     // SERIAL: one row load in flight per wave.  Chosen by the launcher where momentum is written back
     // (read/write mix); the read-only forms (sign_pack, signSGD step) keep all loads of the group in flight.
@@ -37,7 +58,7 @@ __device__ __forceinline__ void worker_group(const StepArgs& a, int m0, int64_t 
     float vv[U][SUB][VEC];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const GT* __restrict__ gp = ROWS::template g<GT>(a, m0 + u) + j0;
+        const GT* __restrict__ gp = rows.g[u] + j0;
 #pragma unroll
         for (int s = 0; s < SUB; ++s) {
             if constexpr (GUARD) {
@@ -51,7 +72,7 @@ __device__ __forceinline__ void worker_group(const StepArgs& a, int m0, int64_t 
     if constexpr (MOM) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const float* vp = ROWS::v(a, m0 + u) + j0;
+            const float* vp = rows.v[u] + j0;
 #pragma unroll
             for (int s = 0; s < SUB; ++s) {
                 if constexpr (GUARD) {
@@ -76,7 +97,7 @@ __device__ __forceinline__ void worker_group(const StepArgs& a, int m0, int64_t 
                     float t = a.omb * gv[u][s][c];
                     vv[u][s][c] = fmaf(a.beta, vv[u][s][c], t);
                 }
-                float* vp = ROWS::v(a, m) + j0 + s * kTile;
+                float* vp = rows.v[u] + j0 + s * kTile;
                 if constexpr (GUARD) store_vals_guarded<float, VEC>(vp, nvalid[s], vv[u][s]);
                 else store_vals<VEC>(vp, vv[u][s]);
             } else {
@@ -119,9 +140,19 @@ __device__ __forceinline__ void step_tiles(const StepArgs& a, int64_t tile0, int
 
     constexpr int U = 2;
     int m = 0;
-    for (; m + U <= a.M; m += U)
-        worker_group<GT, VEC, SUB, MOM, OUT, GUARD, SERIAL, ROWS, U>(a, m, j0, nvalid, lane, tile0, cnt);
-    if (m < a.M) worker_group<GT, VEC, SUB, MOM, OUT, GUARD, SERIAL, ROWS, 1>(a, m, j0, nvalid, lane, tile0, cnt);
+    if (a.M >= U) {
+        RowStarts<GT, U> cur = fetch_rows<GT, MOM, ROWS, U>(a, 0);
+        for (; m + U <= a.M; m += U) {
+            const int mn = (m + 2 * U <= a.M) ? m + U : m;          // the group after this one (or this one again at the end)
+            const RowStarts<GT, U> nxt = fetch_rows<GT, MOM, ROWS, U>(a, mn);
+            worker_group<GT, VEC, SUB, MOM, OUT, GUARD, SERIAL, U>(a, cur, m, j0, nvalid, lane, tile0, cnt);
+            cur = nxt;
+        }
+    }
+    if (m < a.M) {
+        const RowStarts<GT, 1> last = fetch_rows<GT, MOM, ROWS, 1>(a, m);
+        worker_group<GT, VEC, SUB, MOM, OUT, GUARD, SERIAL, 1>(a, last, m, j0, nvalid, lane, tile0, cnt);
+    }
 
 #pragma unroll
     for (int s = 0; s < SUB; ++s) {
