@@ -74,7 +74,7 @@ struct MultiArgs {
 };
 
 template <typename GT, typename XT, bool MOM, bool SERIAL>
-__global__ __launch_bounds__(kBlock) void step_multi_kernel(MultiArgs ma) {
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(5, 5))) void step_multi_kernel(MultiArgs ma) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int64_t unit = blockIdx.x;

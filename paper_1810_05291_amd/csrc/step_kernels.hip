@@ -28,7 +28,7 @@ namespace ssv {
 // after them take the remaining (fewer than 4*SUB + 1) tiles one by one with bounds checks.
 // OUT = false is the lean form without optional outputs (packed signs, packed vote, flips).
 template <typename GT, typename XT, int VEC, int SUB, bool MOM, bool APPLY, bool OUT, bool SERIAL>
-__global__ __launch_bounds__(kBlock) void step_kernel(StepArgs a, int64_t nfull) {
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(5, 5))) void step_kernel(StepArgs a, int64_t nfull) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int64_t lb = blockIdx.x;
