@@ -46,6 +46,7 @@ def parse_args():
                          "(known traffic: 1 GiB read + 1 GiB written per copy) to scale rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--cpu-sample", type=int, default=1 << 22, help="coordinates in the oracle's timed sample")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU time to spend on the oracle's timed sample")
     return ap.parse_args()
 
 
@@ -284,7 +285,7 @@ def main():
             n_cpu += 1
         # keep timing (on copies, so the parity state is not disturbed) until about 10 s of CPU work
         xs, vs = x_ref.copy(), v_ref.copy()
-        while t_cpu < 10.0 and n_cpu < 1000:
+        while t_cpu < args.cpu_seconds and n_cpu < 1000:
             t0 = time.perf_counter()
             ora.signum_step(g_h[n_cpu % len(g_h)], vs, beta, xs, lr)
             t_cpu += time.perf_counter() - t0

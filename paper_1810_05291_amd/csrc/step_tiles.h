@@ -149,7 +149,7 @@ __device__ __forceinline__ void step_tiles(const StepArgs& a, int64_t tile0, int
             cur = nxt;
         }
     }
-    if (m < a.M) {
+    for (; m < a.M; ++m) {                                           // the M mod U workers that are left
         const RowStarts<GT, 1> last = fetch_rows<GT, MOM, ROWS, 1>(a, m);
         worker_group<GT, VEC, SUB, MOM, OUT, GUARD, SERIAL, 1>(a, last, m, j0, nvalid, lane, tile0, cnt);
     }
