@@ -172,6 +172,8 @@ __global__ __launch_bounds__(kBlock) void qsgd_quantize_kernel(QuantArgs a, int6
 }
 
 // ---- 1-way average + update -------------------------------------------------------------------------------
+typedef _Float16 h16x4 __attribute__((ext_vector_type(4)));
+
 struct AggArgs {
     const uint64_t* nonzero;
     const uint64_t* sign;
@@ -185,24 +187,50 @@ struct AggArgs {
 
 // A wavefront owns a tile of 2048 coordinates = 64 dwords of every plane row.  Lane l loads dword l of both planes
 // for every worker (two 256-byte reads per worker per wave) and sums the decoded values of ITS 32 coordinates in 32
-// registers, workers in index order.  The averages then change hands through LDS (a padded per-wave array, no bank
-// conflicts) so that the weight / average accesses are contiguous: lane l takes elements (i * 64 + l) * VEC of the
-// tile in access i.  A first version in which a lane read the plane BYTE of its 4 coordinates per worker was bound by
-// the number of load instructions (30 tiny loads per 4 coordinates at M = 15): 25% of the HBM peak.
+// registers, workers in index order.  Decoding goes through a 256-entry table in LDS: the 4 nonzero bits and 4 sign
+// bits of four neighbouring coordinates index a float4 of {0, +1, -1} factors, and acc <- fma(norm, factor, acc)
+// adds +norm, -norm or +0 exactly (norm finite; a worker whose norm is Inf or NaN takes a mask-based path, because
+// Inf * 0 is not 0).  That is about 1.6 vector operations per worker-coordinate.  Earlier forms: a lane reading
+// the plane BYTE of its 4 coordinates per worker was bound by the number of load instructions (25% of the HBM
+// peak); "acc = keep ? acc +- norm : acc" compiles to compares and EXEC-mask juggling (39%); one-bit signed
+// bit-field extracts and masks take 5 operations per worker-coordinate, which at M = 15 is more ALU time than the
+// kernel's HBM time (55%).
+// The averages then change hands through LDS (a padded per-wave array, no bank conflicts) so that the weight /
+// average accesses are contiguous: lane l takes elements (i * 64 + l) * VEC of the tile in access i.
 template <typename XT, int VEC>
 __global__ __launch_bounds__(kBlock) void qsgd_aggregate_kernel(AggArgs a, int64_t ntiles) {
     constexpr int kTileCoords = kWave * 32;
     constexpr int kPad = 33;                                        // row pitch of a lane's 32 values: odd => conflict-free
     __shared__ float stage[kWavesPerBlock][kWave * kPad];
+    __shared__ h16x4 factor[256];                                   // {0, +1, -1} are exact in half precision
+    {
+        const uint32_t i = threadIdx.x;                             // kBlock == 256: one table entry per thread
+        h16x4 q;
+        q.x = (_Float16)((i & 1u) ? ((i & 16u) ? 1.0f : -1.0f) : 0.0f);
+        q.y = (_Float16)((i & 2u) ? ((i & 32u) ? 1.0f : -1.0f) : 0.0f);
+        q.z = (_Float16)((i & 4u) ? ((i & 64u) ? 1.0f : -1.0f) : 0.0f);
+        q.w = (_Float16)((i & 8u) ? ((i & 128u) ? 1.0f : -1.0f) : 0.0f);
+        factor[i] = q;
+    }
+    __syncthreads();                                                // every thread of the workgroup reaches this
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave;
-    if (tile >= ntiles) return;                                     // wave-uniform; no workgroup barrier is used below
+    if (tile >= ntiles) return;                                     // wave-uniform; no workgroup barrier below
     const int64_t W2 = 2 * ((a.d + 63) / 64);                       // dwords per plane row that exist
     const int64_t dw = tile * kWave + lane;
     const bool have = dw < W2;
     const int64_t row_dw = 2 * a.words_stride;
     const uint32_t* __restrict__ nzp = reinterpret_cast<const uint32_t*>(a.nonzero) + dw;
     const uint32_t* __restrict__ sgp = reinterpret_cast<const uint32_t*>(a.sign) + dw;
+    const int64_t cbase = tile * (int64_t)kTileCoords;
+    const int64_t left = a.d - cbase;                               // > 0
+    const bool full = left >= kTileCoords;                          // wave-uniform
+    constexpr int kAcc = 32 / VEC;
+    float xv[kAcc][VEC];
+    if (full && a.x != nullptr) {                                   // the weights of a full tile are requested first
+#pragma unroll
+        for (int i = 0; i < kAcc; ++i) load_vals<VEC>(static_cast<XT*>(a.x) + cbase + (i * kWave + lane) * VEC, xv[i]);
+    }
     float acc[32];
 #pragma unroll
     for (int c = 0; c < 32; ++c) acc[c] = 0.0f;
@@ -217,12 +245,28 @@ __global__ __launch_bounds__(kBlock) void qsgd_aggregate_kernel(AggArgs a, int64
         }
 #pragma unroll
         for (int k = 0; k < UM; ++k) {                              // workers in index order: the fp32 sum has a fixed order
-            if (m0 + k < a.M) {
-                const float nm = a.norms[m0 + k];
+            if (m0 + k >= a.M) continue;
+            const float nm = a.norms[m0 + k];
+            if ((__float_as_uint(nm) & 0x7f800000u) != 0x7f800000u) {               // finite (workgroup-uniform)
+#pragma unroll
+                for (int q4 = 0; q4 < 8; ++q4) {
+                    const uint32_t idx = ((nz[k] >> (4 * q4)) & 15u) | (((sg[k] >> (4 * q4)) & 15u) << 4);
+                    const h16x4 f = factor[idx];                   // widened exactly inside the mixed-precision fma
+                    acc[4 * q4 + 0] = fmaf(nm, (float)f.x, acc[4 * q4 + 0]);
+                    acc[4 * q4 + 1] = fmaf(nm, (float)f.y, acc[4 * q4 + 1]);
+                    acc[4 * q4 + 2] = fmaf(nm, (float)f.z, acc[4 * q4 + 2]);
+                    acc[4 * q4 + 3] = fmaf(nm, (float)f.w, acc[4 * q4 + 3]);
+                }
+            } else {
+                // Inf or NaN norm: the addend is +norm, -norm or +0, selected by all-ones / all-zeros masks from
+                // one-bit signed bit-field extracts
+                const uint32_t plus = __float_as_uint(nm), minus = plus ^ 0x80000000u;
+                const uint32_t P = nz[k] & sg[k], N = nz[k] & ~sg[k];
 #pragma unroll
                 for (int c = 0; c < 32; ++c) {
-                    const bool keep = (nz[k] >> c) & 1u, pos = (sg[k] >> c) & 1u;
-                    acc[c] = keep ? (pos ? acc[c] + nm : acc[c] - nm) : acc[c];
+                    const uint32_t mp = (uint32_t)__builtin_amdgcn_sbfe((int)P, c, 1);
+                    const uint32_t mn = (uint32_t)__builtin_amdgcn_sbfe((int)N, c, 1);
+                    acc[c] += __uint_as_float((mp & plus) | (mn & minus));
                 }
             }
         }
@@ -234,29 +278,38 @@ __global__ __launch_bounds__(kBlock) void qsgd_aggregate_kernel(AggArgs a, int64
     __builtin_amdgcn_s_waitcnt(0xc07f);                                          // lgkmcnt(0)
     __builtin_amdgcn_wave_barrier();
 
-    const int64_t cbase = tile * (int64_t)kTileCoords;
-    const int64_t left = a.d - cbase;                                            // > 0
-    constexpr int kAcc = 32 / VEC;
-#pragma unroll 4
-    for (int i = 0; i < kAcc; ++i) {
+    if (full) {
+#pragma unroll
+        for (int i = 0; i < kAcc; ++i) {
+            const int off = (i * kWave + lane) * VEC;
+            float av[VEC];
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) av[c] = st[((off + c) >> 5) * kPad + ((off + c) & 31)];
+            if (a.avg_out != nullptr) store_vals<VEC>(a.avg_out + cbase + off, av);
+            if (a.x != nullptr) {
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) xv[i][c] = fmaf(-a.lr, av[c], xv[i][c]);
+                store_vals<VEC>(static_cast<XT*>(a.x) + cbase + off, xv[i]);
+            }
+        }
+        return;
+    }
+    for (int i = 0; i < kAcc; ++i) {                                             // the ragged last tile
         const int off = (i * kWave + lane) * VEC;
         const int64_t r = left - off;
         const int n = r >= VEC ? VEC : (r > 0 ? (int)r : 0);
         if (n == 0) continue;
         float av[VEC];
 #pragma unroll
-        for (int c = 0; c < VEC; ++c) {
-            const int j = off + c;
-            av[c] = st[(j >> 5) * kPad + (j & 31)];
-        }
+        for (int c = 0; c < VEC; ++c) av[c] = st[((off + c) >> 5) * kPad + ((off + c) & 31)];
         if (a.avg_out != nullptr) store_vals_guarded<float, VEC>(a.avg_out + cbase + off, n, av);
         if (a.x != nullptr) {
             XT* xp = static_cast<XT*>(a.x) + cbase + off;
-            float xv[VEC];
-            load_vals_guarded<XT, VEC>(xp, n, xv);
+            float xg[VEC];
+            load_vals_guarded<XT, VEC>(xp, n, xg);
 #pragma unroll
-            for (int c = 0; c < VEC; ++c) xv[c] = fmaf(-a.lr, av[c], xv[c]);
-            store_vals_guarded<XT, VEC>(xp, n, xv);
+            for (int c = 0; c < VEC; ++c) xg[c] = fmaf(-a.lr, av[c], xg[c]);
+            store_vals_guarded<XT, VEC>(xp, n, xg);
         }
     }
 }
