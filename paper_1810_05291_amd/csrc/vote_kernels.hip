@@ -154,7 +154,7 @@ template <int PW, int NPL>
 __global__ __launch_bounds__(kBlock) void vote_kernel(VoteArgs a) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
-    const int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+    const int64_t tile = (int64_t)blockIdx.x * (blockDim.x / kWave) + wave;
     if (tile >= a.ntiles) return;
     const int64_t ndw = 2 * a.W;
     const int64_t dw0 = (tile * kWave + lane) * PW;
@@ -257,14 +257,22 @@ __global__ __launch_bounds__(kBlock) void vote_apply_kernel(VoteArgs a) {
     }
 }
 
+// A vote that moves less than 512 MiB is over in tens of microseconds: what counts then is how evenly the work
+// spreads over the 256 CUs and how soon every CU has loads in flight, not the width of a lane's access.  Such
+// votes run with 8-byte row pieces (twice the wavefronts) in single-wave workgroups.  Measured at the resnet50
+// size: M = 15, 17.0 -> 10.3 us; M = 31, 31.2 -> 17.7 us (72% of the HBM peak).  Large votes keep 16-byte pieces
+// and four-wave workgroups (d = 2^30, M = 255: 78.8% against 66.4% with 8-byte pieces).
+static inline bool small_vote(const VoteArgs& a) { return (int64_t)(a.M + 1) * a.d < (1LL << 32); }
+
 template <int PW, int NPL>
 static hipError_t launch_vote_only(VoteArgs a, hipStream_t s) {
     const int64_t ndw = 2 * a.W;
     a.ntiles = (ndw + (int64_t)kWave * PW - 1) / ((int64_t)kWave * PW);
-    const int64_t grid = (a.ntiles + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int waves = small_vote(a) ? 1 : kWavesPerBlock;
+    const int64_t grid = (a.ntiles + waves - 1) / waves;
     if (grid > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     (void)hipGetLastError();                 // a stale error of an earlier, unrelated call is not this launch's
-    hipLaunchKernelGGL((vote_kernel<PW, NPL>), dim3((unsigned)grid), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL((vote_kernel<PW, NPL>), dim3((unsigned)grid), dim3(waves * kWave), 0, s, a);
     return hipGetLastError();
 }
 
@@ -287,7 +295,8 @@ static hipError_t launch_vote_apply_one(VoteArgs a, hipStream_t s) {
 
 template <int NPL>
 static hipError_t launch_vote_npl(const VoteArgs& a, int x_dt, bool rows16, bool x_vector_ok, hipStream_t s) {
-    if (a.x == nullptr) return rows16 ? launch_vote_only<4, NPL>(a, s) : launch_vote_only<2, NPL>(a, s);
+    if (a.x == nullptr)
+        return (rows16 && !small_vote(a)) ? launch_vote_only<4, NPL>(a, s) : launch_vote_only<2, NPL>(a, s);
     if (x_dt == 0)
         return x_vector_ok ? launch_vote_apply_one<NPL, float, 4>(a, s) : launch_vote_apply_one<NPL, float, 1>(a, s);
     return x_vector_ok ? launch_vote_apply_one<NPL, bf16, 8>(a, s) : launch_vote_apply_one<NPL, bf16, 1>(a, s);
