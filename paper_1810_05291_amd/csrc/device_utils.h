@@ -9,10 +9,24 @@ namespace ssv {
 // Every gradient, momentum and weight element is touched once per step, so the 8- and 16-byte
 // accesses carry the non-temporal hint: measured on MI355X this is worth about 10% of HBM
 // bandwidth on the fused step (the lines do not linger in L2 / Infinity Cache).
+// Every pointer that reaches these helpers is device (global) memory.  Saying so in the type -- instead of leaving
+// a generic pointer, which is all the compiler knows about a pointer it loaded from a table -- gives global_load /
+// global_store with "scalar base + 32-bit lane offset" addressing rather than flat instructions on 64-bit
+// per-lane addresses (which also cost two registers per live pointer).
+#define SSV_GLOBAL __attribute__((address_space(1)))
+#define SSV_CONSTANT __attribute__((address_space(4)))
 template <typename V>
-__device__ __forceinline__ V stream_load(const V* p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ V stream_load(const V* p) {
+    return __builtin_nontemporal_load((const SSV_GLOBAL V*)p);
+}
 template <typename V>
-__device__ __forceinline__ void stream_store(V* p, V v) { __builtin_nontemporal_store(v, p); }
+__device__ __forceinline__ void stream_store(V* p, V v) {
+    __builtin_nontemporal_store(v, (SSV_GLOBAL V*)p);
+}
+// A 64-bit value (a device address) from a read-only table at a wave-uniform index: a scalar load.
+__device__ __forceinline__ uint64_t uniform_table_entry(const void* table, int64_t index) {
+    return ((const SSV_CONSTANT uint64_t*)table)[index];
+}
 
 // Wait until every memory operation this wave has issued has completed.  Placed after each row
 // load of the fused step it keeps ONE load per wave in flight: with 16-20 waves per CU that is
@@ -26,7 +40,7 @@ __device__ __forceinline__ void drain_memory_ops() { asm volatile("s_waitcnt vmc
 template <int VEC>
 __device__ __forceinline__ void load_vals(const float* __restrict__ p, float (&o)[VEC]) {
     if constexpr (VEC == 1) {
-        o[0] = p[0];
+        o[0] = *(const SSV_GLOBAL float*)p;
     } else {
 #pragma unroll
         for (int q = 0; q < VEC / 4; ++q) {
@@ -39,7 +53,7 @@ __device__ __forceinline__ void load_vals(const float* __restrict__ p, float (&o
 template <int VEC>
 __device__ __forceinline__ void load_vals(const bf16* __restrict__ p, float (&o)[VEC]) {
     if constexpr (VEC == 1) {
-        o[0] = bf16_bits_to_f32(p[0].bits);
+        o[0] = bf16_bits_to_f32(((const SSV_GLOBAL bf16*)p)->bits);
     } else if constexpr (VEC == 4) {
         u32x2 t = stream_load(reinterpret_cast<const u32x2*>(p));
         o[0] = __uint_as_float(t.x << 16); o[1] = __uint_as_float(t.x & 0xffff0000u);
@@ -73,7 +87,7 @@ __device__ __forceinline__ void load_vals_guarded(const T* __restrict__ p, int n
 template <int VEC>
 __device__ __forceinline__ void store_vals(float* __restrict__ p, const float (&o)[VEC]) {
     if constexpr (VEC == 1) {
-        p[0] = o[0];
+        *(SSV_GLOBAL float*)p = o[0];
     } else {
 #pragma unroll
         for (int q = 0; q < VEC / 4; ++q) {
@@ -86,7 +100,7 @@ __device__ __forceinline__ void store_vals(float* __restrict__ p, const float (&
 template <int VEC>
 __device__ __forceinline__ void store_vals(bf16* __restrict__ p, const float (&o)[VEC]) {
     if constexpr (VEC == 1) {
-        p[0].bits = (uint16_t)f32_to_bf16_bits(o[0]);
+        ((SSV_GLOBAL bf16*)p)->bits = (uint16_t)f32_to_bf16_bits(o[0]);
     } else if constexpr (VEC == 4) {
         u32x2 t = {f32_to_bf16_bits(o[0]) | (f32_to_bf16_bits(o[1]) << 16),
                    f32_to_bf16_bits(o[2]) | (f32_to_bf16_bits(o[3]) << 16)};

@@ -73,10 +73,38 @@ struct MultiArgs {
     float beta, omb, lr, wd;
 };
 
+// The last, partial unit of a tensor, and every unit of a tensor with a pointer that does not allow vector
+// accesses: bounds-checked tiles, one at a time.  Kept out of line so that its registers do not count against
+// the hot path of the kernel, which sits exactly at the register budget of five waves per SIMD.
+// Takes the tensor's description as plain values (a reference to a StepArgs would force that struct, and with it
+// the hot path's copy, into memory).
+template <typename GT, typename XT, bool MOM>
+__device__ __attribute__((noinline)) void ragged_or_unaligned_unit(const void* g, float* v, void* x, int64_t n, int M,
+                                                                   int T, float beta, float omb, float lr, float wd,
+                                                                   int64_t u, bool aligned, int wave, int lane) {
+    StepArgs a;
+    a.g = g; a.v = v; a.x = x; a.vote_out = nullptr; a.signs_out = nullptr;
+    a.d = n; a.M = M; a.T = T; a.beta = beta; a.omb = omb; a.lr = lr; a.wd = wd; a.has_flip = 0;
+    if (aligned) {
+        constexpr int64_t kTileCoords = (int64_t)kWave * 4;
+        for (int s = 0; s < kStepSub; ++s) {
+            const int64_t tile = u * (kWavesPerBlock * kStepSub) + wave + s * kWavesPerBlock;
+            if (tile * kTileCoords < a.d) step_tiles<GT, XT, 4, 1, MOM, true, false, true, false, TableRows>(a, tile, lane);
+        }
+    } else {
+        // one coordinate per lane: the unit's 4096 coordinates are 64 tiles of 64
+        constexpr int kTilesPerWave = (int)(kUnit / kWave / kWavesPerBlock);
+        for (int s = 0; s < kTilesPerWave; ++s) {
+            const int64_t tile = u * (kUnit / kWave) + wave + (int64_t)s * kWavesPerBlock;
+            if (tile * kWave < a.d) step_tiles<GT, XT, 1, 1, MOM, true, false, true, false, TableRows>(a, tile, lane);
+        }
+    }
+}
+
 template <typename GT, typename XT, bool MOM, bool SERIAL>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(5, 5))) void step_multi_kernel(MultiArgs ma) {
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);      // tell the compiler it is wave-uniform
     const int64_t unit = blockIdx.x;
     const int t = ma.unit_tensor[unit];                       // workgroup-uniform: scalar loads
     const int64_t u = unit - ma.first_unit[t];                // unit inside its tensor
@@ -91,24 +119,13 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(5, 5))) 
     a.beta = ma.beta; a.omb = ma.omb; a.lr = ma.lr; a.wd = ma.wd;
     a.has_flip = 0;
 
-    if (ma.aligned[t]) {
-        constexpr int64_t kTileCoords = (int64_t)kWave * 4;
-        const int64_t tile0 = u * (kWavesPerBlock * kStepSub) + wave;      // 256-coordinate tiles of this tensor
-        if ((u + 1) * kUnit <= a.d) {
-            step_tiles<GT, XT, 4, kStepSub, MOM, true, false, false, SERIAL, TableRows>(a, tile0, lane);
-        } else {
-            for (int s = 0; s < kStepSub; ++s) {
-                const int64_t tile = tile0 + s * kWavesPerBlock;
-                if (tile * kTileCoords < a.d) step_tiles<GT, XT, 4, 1, MOM, true, false, true, false, TableRows>(a, tile, lane);
-            }
-        }
+    if (ma.aligned[t] && (u + 1) * kUnit <= a.d) {
+        // the common case, a whole unit of an aligned tensor: exactly the flat kernel's inner body
+        step_tiles<GT, XT, 4, kStepSub, MOM, true, false, false, SERIAL, TableRows>(
+            a, u * (kWavesPerBlock * kStepSub) + wave, lane);
     } else {
-        // some pointer of the tensor is not aligned for vector accesses: one coordinate per lane
-        constexpr int kTilesPerWave = (int)(kUnit / kWave / kWavesPerBlock);
-        for (int s = 0; s < kTilesPerWave; ++s) {
-            const int64_t tile = u * (kUnit / kWave) + wave + (int64_t)s * kWavesPerBlock;
-            if (tile * kWave < a.d) step_tiles<GT, XT, 1, 1, MOM, true, false, true, false, TableRows>(a, tile, lane);
-        }
+        ragged_or_unaligned_unit<GT, XT, MOM>(a.g, a.v, a.x, a.d, a.M, a.T, a.beta, a.omb, a.lr, a.wd, u,
+                                              ma.aligned[t] != 0, wave, lane);
     }
 }
 

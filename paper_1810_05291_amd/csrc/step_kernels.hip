@@ -30,7 +30,7 @@ namespace ssv {
 template <typename GT, typename XT, int VEC, int SUB, bool MOM, bool APPLY, bool OUT, bool SERIAL>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(5, 5))) void step_kernel(StepArgs a, int64_t nfull) {
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);      // tell the compiler it is wave-uniform
     const int64_t lb = blockIdx.x;
     if (lb < nfull) {
         step_tiles<GT, XT, VEC, SUB, MOM, APPLY, OUT, false, SERIAL>(a, lb * (kWavesPerBlock * SUB) + wave, lane);

@@ -20,10 +20,10 @@ struct FlatRows {
 struct TableRows {
     template <typename GT>
     static __device__ __forceinline__ const GT* g(const StepArgs& a, int m) {
-        return static_cast<const GT* const*>(a.g)[m];
+        return reinterpret_cast<const GT*>(uniform_table_entry(a.g, m));
     }
     static __device__ __forceinline__ float* v(const StepArgs& a, int m) {
-        return reinterpret_cast<float* const*>(a.v)[m];
+        return reinterpret_cast<float*>(uniform_table_entry(a.v, m));
     }
 };
 
@@ -48,9 +48,11 @@ __device__ __forceinline__ RowStarts<GT, U> fetch_rows(const StepArgs& a, int m0
 }
 
 template <typename GT, int VEC, int SUB, bool MOM, bool OUT, bool GUARD, bool SERIAL, int U>
-__device__ __forceinline__ void worker_group(const StepArgs& a, const RowStarts<GT, U>& rows, int m0, int64_t j0,
-                                             const int (&nvalid)[SUB], int lane, int64_t tile0,
-                                             uint32_t (&cnt)[SUB][VEC]) {
+__device__ __forceinline__ void worker_group(const StepArgs& a, const RowStarts<GT, U>& rows, int m0, int64_t jt,
+                                             uint32_t jl, const int (&nvalid)[SUB], int lane, int64_t tile0,
+                                             uint32_t (&cnt)[SUB][(VEC + 1) / 2]) {
+    // jt: first coordinate of the wave's first tile (wave-uniform, so row start + jt stays in scalar registers);
+    // jl: this lane's offset inside a tile (32 bits).  Addresses are then "scalar base + 32-bit lane offset".
     constexpr int64_t kTile = (int64_t)kWave * VEC * kWavesPerBlock;   // a wave's tiles are a block-row apart
     // SERIAL: one row load in flight per wave.  Chosen by the launcher where momentum is written back
     // (read/write mix); the read-only forms (sign_pack, signSGD step) keep all loads of the group in flight.
@@ -58,13 +60,13 @@ __device__ __forceinline__ void worker_group(const StepArgs& a, const RowStarts<
     float vv[U][SUB][VEC];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const GT* __restrict__ gp = rows.g[u] + j0;
 #pragma unroll
         for (int s = 0; s < SUB; ++s) {
+            const GT* __restrict__ gp = (rows.g[u] + (jt + s * kTile)) + jl;       // scalar part first, then the lane's
             if constexpr (GUARD) {
-                load_vals_guarded<GT, VEC>(gp + s * kTile, nvalid[s], gv[u][s]);
+                load_vals_guarded<GT, VEC>(gp, nvalid[s], gv[u][s]);
             } else {
-                load_vals<VEC>(gp + s * kTile, gv[u][s]);
+                load_vals<VEC>(gp, gv[u][s]);
                 if constexpr (SERIAL) drain_memory_ops();
             }
         }
@@ -72,13 +74,13 @@ __device__ __forceinline__ void worker_group(const StepArgs& a, const RowStarts<
     if constexpr (MOM) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const float* vp = rows.v[u] + j0;
 #pragma unroll
             for (int s = 0; s < SUB; ++s) {
+                const float* vp = (rows.v[u] + (jt + s * kTile)) + jl;
                 if constexpr (GUARD) {
-                    load_vals_guarded<float, VEC>(vp + s * kTile, nvalid[s], vv[u][s]);
+                    load_vals_guarded<float, VEC>(vp, nvalid[s], vv[u][s]);
                 } else {
-                    load_vals<VEC>(vp + s * kTile, vv[u][s]);
+                    load_vals<VEC>(vp, vv[u][s]);
                     if constexpr (SERIAL) drain_memory_ops();
                 }
             }
@@ -97,7 +99,7 @@ __device__ __forceinline__ void worker_group(const StepArgs& a, const RowStarts<
                     float t = a.omb * gv[u][s][c];
                     vv[u][s][c] = fmaf(a.beta, vv[u][s][c], t);
                 }
-                float* vp = rows.v[u] + j0 + s * kTile;
+                float* vp = (rows.v[u] + (jt + s * kTile)) + jl;
                 if constexpr (GUARD) store_vals_guarded<float, VEC>(vp, nvalid[s], vv[u][s]);
                 else store_vals<VEC>(vp, vv[u][s]);
             } else {
@@ -109,7 +111,7 @@ __device__ __forceinline__ void worker_group(const StepArgs& a, const RowStarts<
             for (int c = 0; c < VEC; ++c) {
                 b[c] = (vv[u][s][c] >= 0.0f ? 1u : 0u) ^ flip;
                 if constexpr (GUARD) b[c] = (c < nvalid[s]) ? b[c] : 0u;
-                cnt[s][c] += b[c];
+                cnt[s][c >> 1] += b[c] << (16 * (c & 1));      // two 16-bit counters per register (M <= 1023)
             }
             if (OUT && a.signs_out != nullptr)
                 pack_store_tile<VEC>(a.signs_out + (int64_t)m * a.signs_stride, tile0 + s * kWavesPerBlock, a.W, lane, b);
@@ -122,7 +124,9 @@ template <typename GT, typename XT, int VEC, int SUB, bool MOM, bool APPLY, bool
           typename ROWS = FlatRows>
 __device__ __forceinline__ void step_tiles(const StepArgs& a, int64_t tile0, int lane) {
     constexpr int64_t kTile = (int64_t)kWave * VEC * kWavesPerBlock;
-    const int64_t j0 = tile0 * (int64_t)(kWave * VEC) + (int64_t)lane * VEC;
+    const int64_t jt = tile0 * (int64_t)(kWave * VEC);
+    const uint32_t jl = (uint32_t)lane * VEC;
+    const int64_t j0 = jt + jl;
     int nvalid[SUB];
 #pragma unroll
     for (int s = 0; s < SUB; ++s) {
@@ -132,11 +136,13 @@ __device__ __forceinline__ void step_tiles(const StepArgs& a, int64_t tile0, int
             nvalid[s] = r >= VEC ? VEC : (r > 0 ? (int)r : 0);
         }
     }
-    uint32_t cnt[SUB][VEC];
+    // per-coordinate counts of set sign bits, two 16-bit counters to a register: with 64 registers of row data
+    // per wave the kernel sits exactly at the 96-register budget of five waves per SIMD
+    uint32_t cnt[SUB][(VEC + 1) / 2];
 #pragma unroll
     for (int s = 0; s < SUB; ++s)
 #pragma unroll
-        for (int c = 0; c < VEC; ++c) cnt[s][c] = 0;
+        for (int c = 0; c < (VEC + 1) / 2; ++c) cnt[s][c] = 0;
 
     constexpr int U = 2;
     int m = 0;
@@ -145,13 +151,13 @@ __device__ __forceinline__ void step_tiles(const StepArgs& a, int64_t tile0, int
         for (; m + U <= a.M; m += U) {
             const int mn = (m + 2 * U <= a.M) ? m + U : m;          // the group after this one (or this one again at the end)
             const RowStarts<GT, U> nxt = fetch_rows<GT, MOM, ROWS, U>(a, mn);
-            worker_group<GT, VEC, SUB, MOM, OUT, GUARD, SERIAL, U>(a, cur, m, j0, nvalid, lane, tile0, cnt);
+            worker_group<GT, VEC, SUB, MOM, OUT, GUARD, SERIAL, U>(a, cur, m, jt, jl, nvalid, lane, tile0, cnt);
             cur = nxt;
         }
     }
     for (; m < a.M; ++m) {                                           // the M mod U workers that are left
         const RowStarts<GT, 1> last = fetch_rows<GT, MOM, ROWS, 1>(a, m);
-        worker_group<GT, VEC, SUB, MOM, OUT, GUARD, SERIAL, 1>(a, last, m, j0, nvalid, lane, tile0, cnt);
+        worker_group<GT, VEC, SUB, MOM, OUT, GUARD, SERIAL, 1>(a, last, m, jt, jl, nvalid, lane, tile0, cnt);
     }
 
 #pragma unroll
@@ -159,13 +165,13 @@ __device__ __forceinline__ void step_tiles(const StepArgs& a, int64_t tile0, int
         uint32_t vb[VEC];
 #pragma unroll
         for (int c = 0; c < VEC; ++c) {
-            vb[c] = (cnt[s][c] >= (uint32_t)a.T) ? 1u : 0u;
+            vb[c] = (((cnt[s][c >> 1] >> (16 * (c & 1))) & 0xffffu) >= (uint32_t)a.T) ? 1u : 0u;
             if constexpr (GUARD) vb[c] = (c < nvalid[s]) ? vb[c] : 0u;
         }
         if (OUT && a.vote_out != nullptr) pack_store_tile<VEC>(a.vote_out, tile0 + s * kWavesPerBlock, a.W, lane, vb);
         if constexpr (APPLY) {
             if (nvalid[s] > 0) {
-                XT* xp = static_cast<XT*>(a.x) + j0 + s * kTile;
+                XT* xp = (static_cast<XT*>(a.x) + (jt + s * kTile)) + jl;
                 float xv[VEC];
                 if constexpr (GUARD) load_vals_guarded<XT, VEC>(xp, nvalid[s], xv);
                 else load_vals<VEC>(xp, xv);
