@@ -2,6 +2,9 @@
 
 A step is one pass of the whole hot path -- momentum, sign, majority vote, parameter update -- for
 all M simulated workers: one call of ssv_signum_step on gradients that are already resident in HBM.
+The call is given room for the packed signs (signs_out, M*d/8 bytes), so the library runs it in its
+fastest form: momentum + sign + pack row by row (ssv::pack_rows_kernel), then vote + update on the
+packed rows (ssv::vote_apply_kernel).  The one-kernel form (no signs_out) is timed under "other_kernels".
 Prints ONE JSON line.  Besides the headline it carries, under "other_kernels", the figures of every
 other entry point of the library at its own workload (each: milliseconds per launch, algorithmic
 bytes, GB/s, fraction of the 8 TB/s HBM peak), measured in the same process.
@@ -114,7 +117,7 @@ def other_kernels(torch, sv, wl, dev, quick):
     ms = time_launches(torch, lambda i: sv.signum_momentum_pack(grads[i % 4], v, 0.9, signs), n(40))
     out["signum_momentum_pack_resnet50_M15"] = entry(ms, (12 + 1 / 8) * M * d, bytes_per_worker_coordinate=12.125)
 
-    # ---- unfused pipeline: momentum + pack, vote, update (three launches per step)
+    # ---- unfused pipeline: momentum + pack, vote, update (three launches per step, the vote makes a round trip)
     x = wl.gaussian((d,), 0.02, seed=2, device=dev)
     vote = torch.empty((W,), dtype=torch.int64, device=dev)
 
@@ -126,13 +129,36 @@ def other_kernels(torch, sv, wl, dev, quick):
     ms = time_launches(torch, unfused, n(40))
     out["unfused_pipeline_resnet50_M15"] = entry(ms, (12.125 * M + (M + 1) / 8 + 8.125) * d, launches=3)
 
-    # ---- the headline kernel on the natural [M][d] layout (row stride d: rows only 32-byte phased)
+    # ---- the step as ONE kernel (what a call without signs_out runs): all M rows walked inside every workgroup
+    ms = time_launches(torch, lambda i: sv.signum_step(grads[i % 4], v, 0.9, x, 1e-4), n(50), warmup=3)
+    out["signum_step_resnet50_M15_one_kernel"] = entry(ms, (12.0 * M + 8) * d, launches=1,
+                                                       worker_coords_per_s=M * d / ms * 1e3)
+    ms = time_launches(torch, lambda i: sv.signum_step(grads[i % 4], v, 0.9, x, 1e-4, vote_out=vote), n(50), warmup=3)
+    out["signum_step_resnet50_M15_one_kernel_vote_out"] = entry(ms, (12.0 * M + 8 + 1 / 8) * d, launches=1)
+    ms = time_launches(torch, lambda i: sv.signum_step(grads[i % 4], None, 0.0, x, 1e-4), n(50), warmup=3)
+    out["signsgd_step_resnet50_M15_one_kernel"] = entry(ms, (4.0 * M + 8) * d, launches=1, note="no momentum (beta = 0)")
+
+    # ---- the step on the natural [M][d] layout (row stride d: rows only 32-byte phased), both forms
     gnat = [wl.worker_gradients(mu, M, s, base_seed=3000, row_stride=d) for s in range(4)]
     vnat = torch.zeros((M, d), device=dev)
-    ms = time_launches(torch, lambda i: sv.signum_step(gnat[i % 4], vnat, 0.9, x, 1e-4), n(50), warmup=3)
-    out["signum_step_resnet50_M15_natural_stride"] = entry(ms, (12.0 * M + 8) * d, row_stride=d,
+    snat = torch.empty((M, W), dtype=torch.int64, device=dev)
+    ms = time_launches(torch, lambda i: sv.signum_step(gnat[i % 4], vnat, 0.9, x, 1e-4, signs_out=snat), n(50), warmup=3)
+    out["signum_step_resnet50_M15_natural_stride"] = entry(ms, (12.0 * M + 8) * d, row_stride=d, launches=2,
                                                            worker_coords_per_s=M * d / ms * 1e3)
-    del gnat, vnat
+    ms = time_launches(torch, lambda i: sv.signum_step(gnat[i % 4], vnat, 0.9, x, 1e-4), n(50), warmup=3)
+    out["signum_step_resnet50_M15_natural_stride_one_kernel"] = entry(ms, (12.0 * M + 8) * d, row_stride=d, launches=1)
+    del gnat, vnat, snat
+
+    # ---- twice the workers (M = 31) at the same d, two-kernel and one-kernel form
+    M2 = 31
+    g31 = [wl.worker_gradients(mu, M2, s, base_seed=3500, row_stride=stride) for s in range(2)]
+    v31 = torch.zeros((M2, stride), device=dev)[:, :d]
+    s31 = torch.empty((M2, strideW), dtype=torch.int64, device=dev)[:, :W]
+    ms = time_launches(torch, lambda i: sv.signum_step(g31[i % 2], v31, 0.9, x, 1e-4, signs_out=s31), n(30), warmup=3)
+    out["signum_step_resnet50_M31"] = entry(ms, (12.0 * M2 + 8) * d, launches=2, worker_coords_per_s=M2 * d / ms * 1e3)
+    ms = time_launches(torch, lambda i: sv.signum_step(g31[i % 2], v31, 0.9, x, 1e-4), n(30), warmup=3)
+    out["signum_step_resnet50_M31_one_kernel"] = entry(ms, (12.0 * M2 + 8) * d, launches=1)
+    del g31, v31, s31
 
     # ---- the same step over the model's 161 separate parameter tensors (every worker's gradient and momentum of
     # every tensor an allocation of its own, 15 x 161 x 2 of them): one launch through the pointer table
@@ -213,16 +239,20 @@ def other_kernels(torch, sv, wl, dev, quick):
         x = wl.gaussian((chunk,), 0.02, seed=3, device=dev).to(torch.bfloat16).repeat(nch)[:dl].contiguous()
         mu = wl.shared_mean(chunk, seed=4, device=dev)
         g = [wl.worker_gradients(mu, Ml, s, base_seed=7, dtype=torch.bfloat16) for s in range(2)]
+        sg = torch.empty((Ml, chunk // 64), dtype=torch.int64, device=dev)       # packed signs of one chunk (260 MB), reused
 
-        def large_step(i):
+        def large_step(i, scratch=sg):
             for c in range(nch):
                 c0, c1 = c * chunk, min(dl, (c + 1) * chunk)
-                sv.signum_step(g[c % 2][:, :c1 - c0], v[:, c0:c1], 0.9, x[c0:c1], 1e-5)
+                sv.signum_step(g[c % 2][:, :c1 - c0], v[:, c0:c1], 0.9, x[c0:c1], 1e-5,
+                               signs_out=None if scratch is None else scratch[:, :sv.words_for(c1 - c0)])
 
         ms = time_launches(torch, large_step, max(2, n(3)), warmup=1)
-        out["signum_step_bf16_d1.5e9_M31"] = entry(ms, (10.0 * Ml + 4) * dl, launches=nch,
+        out["signum_step_bf16_d1.5e9_M31"] = entry(ms, (10.0 * Ml + 4) * dl, launches=2 * nch,
                                                    worker_coords_per_s=Ml * dl / ms * 1e3)
-        del v, x, g, mu
+        ms = time_launches(torch, lambda i: large_step(i, None), max(2, n(3)), warmup=1)
+        out["signum_step_bf16_d1.5e9_M31_one_kernel"] = entry(ms, (10.0 * Ml + 4) * dl, launches=nch)
+        del v, x, g, mu, sg
     else:
         out["signum_step_bf16_d1.5e9_M31"] = {"skipped": "not enough free HBM for the 186 GB momentum"}
     torch.cuda.empty_cache()
@@ -264,6 +294,8 @@ def main():
     mu = wl.shared_mean(d, seed=1, device=dev)
     x = wl.gaussian((d,), 0.02, seed=2, device=dev)
     v = torch.zeros((M, stride), device=dev)[:, :d]
+    Wd = sv.words_for(d)
+    signs = torch.empty((M, ((Wd + 15) // 16) * 16), dtype=torch.int64, device=dev)[:, :Wd]   # the workers' packed messages
     nsets = max(1, min(args.grad_sets, K + Wm))
     grads = [wl.worker_gradients(mu, M, s, base_seed=1000, row_stride=stride) for s in range(nsets)]
     torch.cuda.synchronize()
@@ -296,7 +328,7 @@ def main():
 
     # ---- warmup (untimed) ------------------------------------------------------------------------
     for s in range(Wm):
-        sv.signum_step(grads[s % nsets], v, beta, x, lr)
+        sv.signum_step(grads[s % nsets], v, beta, x, lr, signs_out=signs)
     torch.cuda.synchronize()
     parity = None
     mismatched = near_zero = sign_exceptions = None
@@ -317,7 +349,7 @@ def main():
     t0 = time.perf_counter()
     ev0.record()                       # on the current stream, the one the library launches on
     for s in range(K):
-        sv.signum_step(grads[(Wm + s) % nsets], v, beta, x, lr)
+        sv.signum_step(grads[(Wm + s) % nsets], v, beta, x, lr, signs_out=signs)
     ev1.record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -328,11 +360,16 @@ def main():
     evs = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
     evs[0].record()
     for s in range(K):
-        sv.signum_step(grads[(Wm + s) % nsets], v, beta, x, lr)
+        sv.signum_step(grads[(Wm + s) % nsets], v, beta, x, lr, signs_out=signs)
         evs[s + 1].record()
     torch.cuda.synchronize()
     per_launch = [evs[s].elapsed_time(evs[s + 1]) for s in range(K)]
     median_ms = statistics.median(per_launch)
+
+    # ---- the step's two kernels one at a time (same arguments as inside the step), K launches each -----
+    pack_ms = time_launches(torch, lambda i: sv.signum_momentum_pack(grads[i % nsets], v, beta, signs), K, warmup=2)
+    vote_ms = time_launches(torch, lambda i: sv.vote_apply(signs, d, x, lr), K, warmup=2)
+    pack_bytes, vote_bytes = (12.0 + 1 / 8) * M * d, (M / 8 + 8.0) * d
 
     algo_bytes = float(M * 12 + 8) * d
     achieved = algo_bytes / (kern_ms * 1e-3) / 1e9
@@ -348,14 +385,26 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "resnet50-sized fused Signum step", "d": d, "M": M, "beta": beta, "lr": lr,
                    "grad_dtype": "f32", "weight_dtype": "f32", "row_stride": stride,
-                   "gradient_sets_cycled": nsets, "kernel": "ssv_signum_step"},
+                   "gradient_sets_cycled": nsets,
+                   "kernel": "ssv_signum_step with signs_out = ssv::pack_rows_kernel + ssv::vote_apply_kernel"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic,
                      "traffic_source": ("profiles/signum_step_resnet50_pmc.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of "
                                         "this kernel on this workload, scaled by a copy of known size; a committed "
                                         "measurement, not taken in this run") if traffic else None,
-                     "kernel_ms": kern_ms, "algorithmic_bytes_per_launch": algo_bytes},
+                     "kernel_ms": kern_ms, "algorithmic_bytes_per_launch": algo_bytes,
+                     "note": "achieved = bytes the fused step must move (188 B per coordinate: g, v in, v out per worker, "
+                             "x in and out) / HIP-event time of the whole step, both kernels; the packed signs the "
+                             "two-kernel form writes and re-reads (2 x M/8 B per coordinate) are not counted",
+                     "kernels": [
+                         {"name": "ssv::pack_rows_kernel (momentum + sign + pack, the dominant kernel)", "ms": pack_ms,
+                          "algorithmic_bytes": pack_bytes, "GB/s": pack_bytes / pack_ms / 1e6,
+                          "frac": pack_bytes / pack_ms / 1e6 / HBM_PEAK_GBS},
+                         {"name": "ssv::vote_apply_kernel (vote + update on the packed rows; its 150 MB working set "
+                                  "is partly served by the 256 MB Infinity Cache here)", "ms": vote_ms,
+                          "algorithmic_bytes": vote_bytes, "GB/s": vote_bytes / vote_ms / 1e6,
+                          "frac": vote_bytes / vote_ms / 1e6 / HBM_PEAK_GBS}]},
         "bytes_per_voted_coordinate": {"algorithmic": algo_bytes / d,
                                        "measured_hbm": (traffic / d) if traffic else None},
         "cpu_baseline": cpu,
@@ -365,7 +414,7 @@ def main():
         "near_zero_sign_exceptions": sign_exceptions,
     }
     if not args.no_other_kernels:
-        del grads, v, x, mu
+        del grads, v, x, mu, signs
         torch.cuda.empty_cache()
         others = other_kernels(torch, sv, wl, dev, args.quick)
         out["other_kernels"] = others

@@ -22,11 +22,12 @@
  * Memory and ownership: every pointer is DEVICE memory owned by the caller unless the argument
  * is documented as host memory.  The library allocates nothing, never frees, and keeps no state
  * between calls apart from one measurement switch read from the environment on first use:
- *     SSV_TUNE_STEP_SERIAL=0   let the momentum forms of the fused step (ssv_signum_step with v,
+ *     SSV_TUNE_STEP_SERIAL=0   let the momentum forms of the gradient-side kernels (ssv_signum_step with v,
  *                              ssv_signum_momentum_pack) keep all row loads of a worker group in
  *                              flight instead of one load per wavefront at a time.  Results are
- *                              identical; on MI355X it is about 10% slower.  It exists so that the
- *                              two schedules can be profiled against each other; leave it unset.  Matrices are row-major, one row per worker, with the row stride given in
+ *                              identical; on MI355X it is slower.  It exists so that the two
+ *                              schedules can be profiled against each other; leave it unset.
+ * Matrices are row-major, one row per worker, with the row stride given in
  * elements (or in 64-bit words for packed rows).  Inputs must not overlap outputs.  v and x are
  * updated in place.
  *
@@ -121,7 +122,13 @@ int ssv_vote_apply(const uint64_t* signs, int M, int64_t d, int64_t signs_row_st
  *   v != NULL    Signum: v is updated in place as in ssv_signum_momentum_pack.
  *   vote_out     optional, ceil(d/64) words: the packed vote.
  *   signs_out    optional, M packed rows (stride signs_row_stride_words): what each worker
- *                transmitted (after worker_flip).
+ *                transmitted (after worker_flip).  With momentum this buffer also selects the
+ *                FASTEST form of the call: given it, the step runs as two kernels -- momentum +
+ *                sign + pack one worker row after the other, then vote + update on the packed rows
+ *                -- which on MI355X sustains 81% of the HBM peak against 75% for the single kernel
+ *                that walks all M rows at once (72% at M = 31, 69% with unpadded rows, where the
+ *                two-kernel form still reaches 80% and 77%).  Results are bit-identical.  Pass it
+ *                whenever M * ceil(d/64) * 8 bytes can be spared.
  *   worker_flip  optional, HOST memory, M bytes: nonzero = that worker transmits the negation of
  *                its sign vector (the sign-inverting adversary of Definition 1 / Section 4.1).
  *                Its momentum stays honest.  Read before the call returns.

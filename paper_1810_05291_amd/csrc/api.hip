@@ -65,8 +65,22 @@ static int step_common(const void* g, int g_dt, float* v, int M, int64_t d, int6
     }
     bool vec = rows_vector_ok(g, g_row_stride, elem_size(g_dt), M);
     if (v != nullptr) vec = vec && rows_vector_ok(v, v_row_stride, 4, M);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (x != nullptr && v != nullptr && signs_out != nullptr) {
+        // Signum with room for the packed signs: momentum + pack row by row, then vote + update on the packed rows.
+        // Same results as the one-kernel step, about 8% faster on MI355X (see step_kernels.hip).
+        StepArgs p = a;
+        p.x = nullptr;
+        p.vote_out = nullptr;
+        if (hipError_t e = launch_step(p, g_dt, x_dt, vec, s)) return hip_status(e);
+        VoteArgs va = {};
+        va.signs = signs_out; va.vote_out = vote_out; va.x = x;
+        va.d = d; va.W = W; va.stride_words = signs_row_stride_words; va.M = M; va.lr = lr; va.wd = wd;
+        const bool rows16 = rows_vector_ok(signs_out, signs_row_stride_words, 8, M) && aligned(vote_out, 16);
+        return hip_status(launch_vote(va, x_dt, rows16, aligned(x, 16), s));
+    }
     if (x != nullptr) vec = vec && aligned(x, 16);
-    return hip_status(launch_step(a, g_dt, x_dt, vec, static_cast<hipStream_t>(stream)));
+    return hip_status(launch_step(a, g_dt, x_dt, vec, s));
 }
 
 static int vote_common(const uint64_t* signs, int M, int64_t d, int64_t stride_words, void* x, int x_dt, float lr,

@@ -54,9 +54,11 @@ def test_bench_copy_copies(sv):
         sv.bench_copy(src[1:5], dst[1:5])            # not 16-byte aligned
 
 
-def test_fused_step_replays_in_a_hip_graph(sv):
+@pytest.mark.parametrize("with_signs", [False, True])
+def test_fused_step_replays_in_a_hip_graph(sv, with_signs):
     # the library only launches kernels (no allocation, no memset), so a call can be captured;
-    # every replay is one more optimiser step and must match eager execution bit for bit
+    # every replay is one more optimiser step and must match eager execution bit for bit.
+    # with_signs: the call is given room for the packed signs and runs as two kernels, both captured.
     M, d = 15, 200_003
     mu = wl.shared_mean(d, seed=3, device=DEV)
     g = wl.worker_gradients(mu, M, 0, base_seed=40)
@@ -65,12 +67,14 @@ def test_fused_step_replays_in_a_hip_graph(sv):
     x_e, v_e = x_g.clone(), v_g.clone()
     vote_g = torch.zeros((sv.words_for(d),), dtype=torch.int64, device=DEV)
     vote_e = torch.zeros_like(vote_g)
+    signs_g = torch.zeros((M, sv.words_for(d)), dtype=torch.int64, device=DEV) if with_signs else None
+    signs_e = None if signs_g is None else torch.zeros_like(signs_g)
     graph = torch.cuda.CUDAGraph()
     side = torch.cuda.Stream(device=DEV)
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
         with torch.cuda.graph(graph, stream=side):
-            sv.signum_step(g, v_g, 0.9, x_g, 1e-4, vote_out=vote_g)
+            sv.signum_step(g, v_g, 0.9, x_g, 1e-4, vote_out=vote_g, signs_out=signs_g)
     torch.cuda.synchronize()
     # capture does not execute: state is still the initial one
     assert torch.equal(x_g, x_e) and torch.equal(v_g, v_e)
@@ -78,11 +82,13 @@ def test_fused_step_replays_in_a_hip_graph(sv):
     g_h = _host(g)
     for step in range(4):
         graph.replay()
-        sv.signum_step(g, v_e, 0.9, x_e, 1e-4, vote_out=vote_e)       # eager work between replays
+        sv.signum_step(g, v_e, 0.9, x_e, 1e-4, vote_out=vote_e, signs_out=signs_e)       # eager work between replays
         torch.cuda.synchronize()
-        vote_ref, _ = ora.signum_step(g_h, v_ref, 0.9, x_ref, 1e-4)
+        vote_ref, signs_ref = ora.signum_step(g_h, v_ref, 0.9, x_ref, 1e-4, want_signs=True)
         assert torch.equal(x_g, x_e) and torch.equal(v_g, v_e) and torch.equal(vote_g, vote_e), f"replay {step}"
         assert np.array_equal(_host(x_g), x_ref) and np.array_equal(_host(vote_g), vote_ref)
+        if with_signs:
+            assert torch.equal(signs_g, signs_e) and np.array_equal(_host(signs_g), signs_ref)
 
 
 def _quadratic_run(sv, M, adversaries, steps, mode, seed):

@@ -212,9 +212,13 @@ def _step_case(sv, M, d, g_dtype, x_dtype, beta, wd, steps, pad=0, flip=None, mo
         v_ref = np.zeros((M, d), np.float32)
     W = sv.words_for(d)
     near_zero = 0
-    # a twin state stepped through the form without optional outputs (a separate kernel instantiation)
+    # Twin states.  A Signum call that gives room for the packed signs runs as two kernels (momentum + pack row by
+    # row, then vote + update on the packed rows); without signs_out it is one kernel, in a lean instantiation
+    # when no optional output or flip is asked for.  All three forms must agree bit for bit.
     x_lean = x.clone()
     v_lean = None if v is None else v.clone()
+    x_one = x.clone()
+    v_one = None if v is None else v.clone()
     for step in range(steps):
         g = wl.worker_gradients(mu, M, step, base_seed=500, noise_std=noise, dtype=g_dtype, row_stride=d + pad)
         vote_buf = torch.full((W + 2,), -1, dtype=torch.int64, device=DEV)
@@ -250,6 +254,12 @@ def _step_case(sv, M, d, g_dtype, x_dtype, beta, wd, steps, pad=0, flip=None, mo
         assert np.array_equal(wl.to_numpy(vote), vote_ref)
         x_gpu = wl.to_numpy(x.contiguous())
         assert np.array_equal(x_gpu, x_ref)
+        vote_one = torch.full((W + 2,), -1, dtype=torch.int64, device=DEV)
+        sv.signum_step(g, v_one, beta, x_one, lr, wd, vote_out=vote_one[:W], worker_flip=flip)
+        torch.cuda.synchronize()
+        assert (vote_one[W:] == -1).all() and torch.equal(vote_one[:W], vote), "one-kernel form disagrees (vote)"
+        assert torch.equal(x_one, x), "one-kernel form disagrees (weights)"
+        assert v is None or torch.equal(v_one, v), "one-kernel form disagrees (momentum)"
         if flip is None:
             sv.signum_step(g, v_lean, beta, x_lean, lr, wd)
             torch.cuda.synchronize()
