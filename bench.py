@@ -172,6 +172,12 @@ def other_kernels(torch, sv, wl, dev, quick):
     out["signum_step_multi_resnet50_161_tensors_M15"] = entry(ms, (12.0 * M + 8) * d, tensors=len(sizes), launches=1,
                                                                plan_bytes=plan.nbytes,
                                                                worker_coords_per_s=M * d / ms * 1e3)
+    mws = sv.multi_workspace(plan)
+    ms = time_launches(torch, lambda i: sv.signum_step_multi(plan, 0.9, 1e-4, workspace=mws), n(50), warmup=3)
+    out["signum_step_multi_ws_resnet50_161_tensors_M15"] = entry(ms, (12.0 * M + 8) * d, tensors=len(sizes), launches=2,
+                                                                  workspace_bytes=mws.numel() * 8,
+                                                                  worker_coords_per_s=M * d / ms * 1e3)
+    del mws
     # what a caller without it pays first: copying every worker's 161 gradient tensors into the flat rows
     flat = grads[0]
 

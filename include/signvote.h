@@ -122,11 +122,11 @@ int ssv_vote_apply(const uint64_t* signs, int M, int64_t d, int64_t signs_row_st
  *   v != NULL    Signum: v is updated in place as in ssv_signum_momentum_pack.
  *   vote_out     optional, ceil(d/64) words: the packed vote.
  *   signs_out    optional, M packed rows (stride signs_row_stride_words): what each worker
- *                transmitted (after worker_flip).  With momentum this buffer also selects the
- *                FASTEST form of the call: given it, the step runs as two kernels -- momentum +
- *                sign + pack one worker row after the other, then vote + update on the packed rows
- *                -- which on MI355X sustains 81% of the HBM peak against 75% for the single kernel
- *                that walks all M rows at once (72% at M = 31, 69% with unpadded rows, where the
+ *                transmitted (after worker_flip).  This buffer also selects the FASTEST form of
+ *                the call: given it, the step runs as two kernels -- (momentum +) sign + pack one
+ *                worker row after the other, then vote + update on the packed rows -- which for
+ *                Signum on MI355X sustains 81% of the HBM peak against 75% for the single kernel
+ *                that walks all M rows at once (71% at M = 31, 69% with unpadded rows, where the
  *                two-kernel form still reaches 80% and 77%).  Results are bit-identical.  Pass it
  *                whenever M * ceil(d/64) * 8 bytes can be spared.
  *   worker_flip  optional, HOST memory, M bytes: nonzero = that worker transmits the negation of
@@ -169,6 +169,21 @@ int ssv_multi_plan_fill(void* plan_host, size_t plan_bytes, int T, int M, const 
                         const void* const* g, int g_dt, float* const* v);
 int ssv_signum_step_multi(const void* plan_host, const void* plan_device, float beta, float lr, float weight_decay,
                           void* stream);
+
+/*
+ * ssv_signum_step_multi in its faster, two-kernel form (Section 4, tensor fusion; Algorithm 1): momentum + sign +
+ * pack one worker after the other with the packed signs written to `workspace`, then vote + update on the packed
+ * rows -- the multi-tensor counterpart of giving `signs_out` to ssv_signum_step.  Same plan, same results.
+ *   workspace        device memory owned by the caller, 16-byte aligned (128 recommended), at least
+ *                    ssv_multi_workspace_bytes(plan_host) = M * 64 * (units of the plan) * 8 bytes, i.e. about
+ *                    M * d / 8 bytes; contents on entry are irrelevant; on return it holds every worker's packed
+ *                    signs (tensor t's words of worker m start at word m * stride + 64 * (units before t)).
+ *                    Two calls that overlap in time must not share it.
+ * ssv_multi_workspace_bytes returns 0 for a pointer that does not hold a filled plan.
+ */
+size_t ssv_multi_workspace_bytes(const void* plan_host);
+int ssv_signum_step_multi_ws(const void* plan_host, const void* plan_device, void* workspace, size_t workspace_bytes,
+                             float beta, float lr, float weight_decay, void* stream);
 
 /* Static, NUL-terminated description of a status code (host memory, never freed). */
 const char* ssv_status_string(int status);

@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     bench_copy,
     MultiTensorPlan,
     signum_step_multi,
+    multi_workspace,
     SSV_QSGD_L2,
     SSV_QSGD_MAX,
     qsgd_workspace,

@@ -62,6 +62,10 @@ def load_library():
         lib.ssv_multi_plan_fill.restype = _c_int
         lib.ssv_signum_step_multi.argtypes = [_c_p, _c_p, _c_f, _c_f, _c_f, _c_p]
         lib.ssv_signum_step_multi.restype = _c_int
+        lib.ssv_multi_workspace_bytes.argtypes = [_c_p]
+        lib.ssv_multi_workspace_bytes.restype = ctypes.c_size_t
+        lib.ssv_signum_step_multi_ws.argtypes = [_c_p, _c_p, _c_p, ctypes.c_size_t, _c_f, _c_f, _c_f, _c_p]
+        lib.ssv_signum_step_multi_ws.restype = _c_int
         lib.ssv_qsgd_workspace_bytes.argtypes = [_c_int]
         lib.ssv_qsgd_workspace_bytes.restype = ctypes.c_size_t
         lib.ssv_qsgd_norms.argtypes = [_c_p, _c_int, _c_int, _c_i64, _c_i64, _c_int, _c_p, _c_p, ctypes.c_size_t, _c_p]
@@ -322,11 +326,29 @@ class MultiTensorPlan:
         self._keep = (list(params), [list(r) for r in grads], None if momenta is None else [list(r) for r in momenta])
 
 
-def signum_step_multi(plan, beta, lr, weight_decay=0.0):
-    """One fused iteration of Algorithm 1 over all tensors of the plan, in one launch."""
-    _check("ssv_signum_step_multi",
-           load_library().ssv_signum_step_multi(plan.host.data_ptr(), plan.device.data_ptr(), float(beta), float(lr),
-                                                float(weight_decay), _stream(plan.dev)))
+def multi_workspace(plan):
+    """A new device buffer of the size ssv_signum_step_multi_ws needs for this plan (the workers' packed signs)."""
+    nbytes = load_library().ssv_multi_workspace_bytes(plan.host.data_ptr())
+    if nbytes == 0:
+        raise ValueError("not a filled plan")
+    return torch.empty((nbytes // 8,), dtype=torch.int64, device=plan.dev)
+
+
+def signum_step_multi(plan, beta, lr, weight_decay=0.0, workspace=None):
+    """One iteration of Algorithm 1 over all tensors of the plan: one launch, or -- with a workspace from
+    multi_workspace(plan) -- the faster two-kernel form (pack row by row, then vote + update)."""
+    lib = load_library()
+    if workspace is None:
+        _check("ssv_signum_step_multi",
+               lib.ssv_signum_step_multi(plan.host.data_ptr(), plan.device.data_ptr(), float(beta), float(lr),
+                                         float(weight_decay), _stream(plan.dev)))
+        return
+    if workspace.dtype != torch.int64 or not workspace.is_contiguous() or workspace.device != plan.device.device:
+        raise ValueError("workspace must be a contiguous int64 tensor on the plan's device")
+    _check("ssv_signum_step_multi_ws",
+           lib.ssv_signum_step_multi_ws(plan.host.data_ptr(), plan.device.data_ptr(), workspace.data_ptr(),
+                                        workspace.numel() * 8, float(beta), float(lr), float(weight_decay),
+                                        _stream(plan.dev)))
 
 
 # ---- ternary QSGD (include/signvote_qsgd.h) ----------------------------------------------------------------

@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsignvote.so")
 SOURCES = ["api.hip", "step_kernels.hip", "multi_kernels.hip", "vote_kernels.hip", "qsgd_kernels.hip", "bench_copy.hip"]
-HEADERS = ["common.h", "device_utils.h", "step_tiles.h", os.path.join("..", "..", "include", "signvote.h"),
+HEADERS = ["common.h", "device_utils.h", "step_tiles.h", "vote_tiles.h", os.path.join("..", "..", "include", "signvote.h"),
            os.path.join("..", "..", "include", "signvote_bench.h"), os.path.join("..", "..", "include", "signvote_qsgd.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -1,6 +1,6 @@
 """Plumbing for real models with many parameter tensors: the tensor fusion that Section 4 of the paper
-credits with a speed-up of compression and communication.  Two ways to get one kernel launch per step
-however many tensors the model has:
+credits with a speed-up of compression and communication.  Two ways to get one library call per step (two
+kernel launches: pack row by row, then vote + update) however many tensors the model has:
 
 SignumMajorityVote       lays the tensors out back to back in ONE flat buffer, once, and hands out views for
                          the parameters and for each simulated worker's gradients.  The step itself copies
@@ -8,7 +8,7 @@ SignumMajorityVote       lays the tensors out back to back in ONE flat buffer, o
                          model whose autograd leaves gradients in tensors of its own pays one copy per
                          worker per step to move them there.
 SignumMajorityVoteMulti  takes the weight tensors and every worker's gradient tensors where they are (a table
-                         of device addresses, built once) and runs the fused step over the concatenated index
+                         of device addresses, built once) and runs the step over the concatenated index
                          space with per-tensor ragged ends: no copy at all.
 
 Only memory plumbing lives here; all arithmetic is in libsignvote.
@@ -52,7 +52,7 @@ class SignumMajorityVote:
 
     params            list of views into the flat weight vector (update happens in place)
     grads[m]          list of views into worker m's flat gradient row: write gradients there
-    step()            one fused launch: momentum, sign, vote, update for all workers
+    step()            one library call: momentum, sign, vote, update for all workers
     """
 
     def __init__(self, shapes, num_workers, lr=1e-4, beta=0.9, weight_decay=0.0, device="cuda:0",
@@ -70,11 +70,14 @@ class SignumMajorityVote:
         self.v = torch.zeros((self.M, stride_v), dtype=torch.float32, device=device)[:, :d] if self.beta > 0 else None
         self.params = self.layout.views(self.x)
         self.grads = [self.layout.views(self.g[m]) for m in range(self.M)]
+        # room for what the workers transmit (M * d / 8 bytes): with it the library runs the step in its fastest form
+        W = _b.words_for(d)
+        self.signs = torch.empty((self.M, ((W + 15) // 16) * 16), dtype=torch.int64, device=device)[:, :W]
         self.steps = 0
 
     def step(self, worker_flip=None, vote_out=None):
         _b.signum_step(self.g, self.v, self.beta, self.x, self.lr, self.weight_decay, vote_out=vote_out,
-                       worker_flip=worker_flip)
+                       signs_out=self.signs, worker_flip=worker_flip)
         self.steps += 1
 
     def state_dict(self):
@@ -95,7 +98,7 @@ class SignumMajorityVoteMulti:
     worker_grads    M lists of T gradient tensors (worker m's gradient of tensor t); the same tensor objects
                     must be refilled in place every step (their addresses are in the plan)
     Momenta (fp32) are allocated here, one 128-byte aligned slice per tensor in one buffer per worker.
-    step()          one fused launch over all tensors
+    step()          one library call over all tensors
     """
 
     def __init__(self, params, worker_grads, lr=1e-4, beta=0.9, weight_decay=0.0):
@@ -113,8 +116,9 @@ class SignumMajorityVoteMulti:
             self._vbuf = torch.zeros((self.M, max(off, 32)), dtype=torch.float32, device=dev)
             self.momenta = [[self._vbuf[m, o:o + p.numel()] for o, p in zip(offs, self.params)] for m in range(self.M)]
         self.plan = _b.MultiTensorPlan(self.params, self.worker_grads, self.momenta)
+        self.workspace = _b.multi_workspace(self.plan)      # the workers' packed signs: selects the two-kernel form
         self.steps = 0
 
     def step(self):
-        _b.signum_step_multi(self.plan, self.beta, self.lr, self.weight_decay)
+        _b.signum_step_multi(self.plan, self.beta, self.lr, self.weight_decay, workspace=self.workspace)
         self.steps += 1

@@ -33,6 +33,7 @@ def test_header_symbols_are_exported(lib):
     assert {"ssv_sign_pack", "ssv_signum_momentum_pack", "ssv_majority_vote", "ssv_apply_sign_update",
             "ssv_vote_apply", "ssv_signum_step", "ssv_status_string", "ssv_version", "ssv_bench_copy",
             "ssv_multi_plan_bytes", "ssv_multi_plan_fill", "ssv_signum_step_multi",
+            "ssv_multi_workspace_bytes", "ssv_signum_step_multi_ws", "ssv_qsgd_norms_static",
             "ssv_qsgd_workspace_bytes", "ssv_qsgd_norms", "ssv_qsgd_quantize", "ssv_qsgd_aggregate_apply"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in signvote.h but not exported"
@@ -143,8 +144,22 @@ def test_multi_tensor_plan_is_built_on_the_host(lib):
     assert step(host, 0x1000, 0.9, float("inf"), 0.0, None) == -5
     junk = np.zeros(64, np.int64)
     assert step(junk.ctypes.data, 0x1000, 0.9, 1e-3, 0.0, None) == -2         # not a plan
+    # the two-kernel form: its workspace holds 64 words per unit and worker
+    wsb = lib.ssv_multi_workspace_bytes
+    wsb.argtypes, wsb.restype = [ctypes.c_void_p], ctypes.c_size_t
+    assert wsb(host) == M * 8 * 64 * 8 and wsb(None) == 0 and wsb(junk.ctypes.data) == 0
+    step_ws = lib.ssv_signum_step_multi_ws
+    step_ws.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float, ctypes.c_float,
+                        ctypes.c_float, ctypes.c_void_p]
+    need = wsb(host)
+    assert step_ws(host, 0x1000, None, need, 0.9, 1e-3, 0.0, None) == -1
+    assert step_ws(host, 0x1000, 0x2008, need, 0.9, 1e-3, 0.0, None) == -3
+    assert step_ws(host, 0x1000, 0x2000, need - 1, 0.9, 1e-3, 0.0, None) == -2
+    assert step_ws(host, 0x1000, 0x2000, need, 1.5, 1e-3, 0.0, None) == -5
+    assert step_ws(junk.ctypes.data, 0x1000, 0x2000, need, 0.9, 1e-3, 0.0, None) == -2
     assert fill(host, nbytes, T, M, n, xs, 0, gs, 0, None) == 0               # signSGD plan: no momentum
     assert step(host, 0x1000, 0.9, 1e-3, 0.0, None) == -5                     # momentum asked without v
+    assert step_ws(host, 0x1000, 0x2000, need, 0.9, 1e-3, 0.0, None) == -5
 
 
 def test_qsgd_argument_validation_needs_no_device(lib):

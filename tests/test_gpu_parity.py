@@ -484,14 +484,16 @@ def _ragged_sizes(rng, T):
     return sizes
 
 
+@pytest.mark.parametrize("two_kernels", [False, True])
 @pytest.mark.parametrize("g_dtype,x_dtype,momentum", [(torch.float32, torch.float32, True),
                                                       (torch.bfloat16, torch.bfloat16, True),
                                                       (torch.float32, torch.bfloat16, False),
                                                       (torch.bfloat16, torch.float32, True)])
-def test_step_multi_tensor_ragged(sv, g_dtype, x_dtype, momentum):
+def test_step_multi_tensor_ragged(sv, g_dtype, x_dtype, momentum, two_kernels):
     # 60 tensors of ragged sizes, every worker's gradient / momentum of every tensor an allocation of its own;
     # every fifth tensor sits at an odd element offset (no vector alignment: the one-element-per-lane path).
-    # ONE launch per step; the oracle runs Algorithm 1 tensor by tensor.
+    # ONE launch per step -- or, with a workspace for the packed signs, the two-kernel form, whose workspace must
+    # then hold exactly what every worker transmitted.  The oracle runs Algorithm 1 tensor by tensor.
     M, T, steps = 7, 60, 3
     beta = 0.9 if momentum else 0.0
     lr, wd = (1e-4, 0.0) if x_dtype == torch.float32 else (1e-5, 0.0)
@@ -516,6 +518,13 @@ def test_step_multi_tensor_ragged(sv, g_dtype, x_dtype, momentum):
             vbufs.append(b), moms.append(list(v))
     plan = sv.MultiTensorPlan(list(params), grads, moms if momentum else None)
     assert plan.numel == sum(sizes) and plan.T == T and plan.M == M
+    ws = None
+    units = [(n + 4095) // 4096 for n in sizes]
+    first_unit = np.concatenate([[0], np.cumsum(units)])
+    if two_kernels:
+        ws = sv.multi_workspace(plan)
+        assert ws.numel() == M * 64 * int(first_unit[-1])
+        ws.fill_(-1)                                           # stale contents must not matter
     x_ref = [wl.to_numpy(p.contiguous()).copy() for p in params]
     v_ref = [np.zeros((M, n), np.float32) for n in sizes] if momentum else [None] * T
     mus = [wl.shared_mean(n, seed=500 + t, device=DEV) for t, n in enumerate(sizes)]
@@ -524,12 +533,16 @@ def test_step_multi_tensor_ragged(sv, g_dtype, x_dtype, momentum):
             gt = wl.worker_gradients(mus[t], M, step, base_seed=9000 + 31 * t, dtype=g_dtype)
             for m in range(M):
                 grads[m][t].copy_(gt[m])
-        sv.signum_step_multi(plan, beta, lr, wd)
+        sv.signum_step_multi(plan, beta, lr, wd, workspace=ws)
         torch.cuda.synchronize()
+        ws_h = None if ws is None else wl.to_numpy(ws).view(np.uint64).reshape(M, -1)
         for t, n in enumerate(sizes):
             g_h = np.stack([wl.to_numpy(grads[m][t].contiguous()) for m in range(M)])
-            ora.signum_step(g_h, v_ref[t], beta, x_ref[t], lr, wd)
+            _, signs_ref = ora.signum_step(g_h, v_ref[t], beta, x_ref[t], lr, wd, want_signs=True)
             assert np.array_equal(wl.to_numpy(params[t].contiguous()), x_ref[t]), f"weights of tensor {t} (n={n}), step {step}"
+            if ws_h is not None:
+                w0 = 64 * int(first_unit[t])
+                assert np.array_equal(ws_h[:, w0:w0 + signs_ref.shape[1]], signs_ref), f"packed signs of tensor {t} (n={n})"
             if momentum:
                 v_gpu = np.stack([wl.to_numpy(moms[m][t].contiguous()) for m in range(M)])
                 assert np.array_equal(v_gpu, v_ref[t]), f"momentum of tensor {t} (n={n}), step {step}"
@@ -553,12 +566,19 @@ def test_step_multi_equals_flat_step_on_one_large_tensor(sv):
     v_flat = torch.zeros((M, d), device=DEV)
     v_rows = [torch.zeros((d,), device=DEV) for _ in range(M)]
     plan = sv.MultiTensorPlan([x_multi], [[g[m].clone()] for m in range(M)], [[v_rows[m]] for m in range(M)])
+    x_ws = x_flat.clone()
+    v_ws = [torch.zeros((d,), device=DEV) for _ in range(M)]
+    plan_ws = sv.MultiTensorPlan([x_ws], [[g[m].clone()] for m in range(M)], [[v_ws[m]] for m in range(M)])
+    ws = sv.multi_workspace(plan_ws)
     for _ in range(3):
         sv.signum_step(g, v_flat, 0.9, x_flat, 1e-4)
         sv.signum_step_multi(plan, 0.9, 1e-4)
+        sv.signum_step_multi(plan_ws, 0.9, 1e-4, workspace=ws)
     torch.cuda.synchronize()
-    assert torch.equal(x_flat, x_multi)
-    assert all(torch.equal(v_flat[m], v_rows[m]) for m in range(M))
+    assert torch.equal(x_flat, x_multi) and torch.equal(x_flat, x_ws)
+    assert all(torch.equal(v_flat[m], v_rows[m]) and torch.equal(v_flat[m], v_ws[m]) for m in range(M))
+    with pytest.raises(sv.SignvoteError):
+        sv.signum_step_multi(plan_ws, 0.9, 1e-4, workspace=ws[:-1])         # one word short
 
 
 def test_multi_plan_rejects_bad_tensor_lists(sv):
