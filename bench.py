@@ -37,6 +37,9 @@ def parse_args():
                     help="round row strides of the headline run up to a multiple of this many elements "
                          "(32 fp32 = 128 bytes; 1 = the natural [M][d] layout)")
     ap.add_argument("--grad-sets", type=int, default=8, help="distinct pre-generated gradient sets that are cycled")
+    ap.add_argument("--one-kernel", action="store_true",
+                    help="time the step WITHOUT room for the packed signs: the library then runs its one-kernel form "
+                         "(ssv::step_kernel, all M rows walked inside every workgroup); for A/B profiles")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-kernels", action="store_true",
                     help="skip the secondary measurements (copy yardstick, unfused entry points, natural-stride run, "
@@ -302,6 +305,7 @@ def main():
     v = torch.zeros((M, stride), device=dev)[:, :d]
     Wd = sv.words_for(d)
     signs = torch.empty((M, ((Wd + 15) // 16) * 16), dtype=torch.int64, device=dev)[:, :Wd]   # the workers' packed messages
+    step_signs = None if args.one_kernel else signs
     nsets = max(1, min(args.grad_sets, K + Wm))
     grads = [wl.worker_gradients(mu, M, s, base_seed=1000, row_stride=stride) for s in range(nsets)]
     torch.cuda.synchronize()
@@ -334,7 +338,7 @@ def main():
 
     # ---- warmup (untimed) ------------------------------------------------------------------------
     for s in range(Wm):
-        sv.signum_step(grads[s % nsets], v, beta, x, lr, signs_out=signs)
+        sv.signum_step(grads[s % nsets], v, beta, x, lr, signs_out=step_signs)
     torch.cuda.synchronize()
     parity = None
     mismatched = near_zero = sign_exceptions = None
@@ -355,7 +359,7 @@ def main():
     t0 = time.perf_counter()
     ev0.record()                       # on the current stream, the one the library launches on
     for s in range(K):
-        sv.signum_step(grads[(Wm + s) % nsets], v, beta, x, lr, signs_out=signs)
+        sv.signum_step(grads[(Wm + s) % nsets], v, beta, x, lr, signs_out=step_signs)
     ev1.record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -366,20 +370,30 @@ def main():
     evs = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
     evs[0].record()
     for s in range(K):
-        sv.signum_step(grads[(Wm + s) % nsets], v, beta, x, lr, signs_out=signs)
+        sv.signum_step(grads[(Wm + s) % nsets], v, beta, x, lr, signs_out=step_signs)
         evs[s + 1].record()
     torch.cuda.synchronize()
     per_launch = [evs[s].elapsed_time(evs[s + 1]) for s in range(K)]
     median_ms = statistics.median(per_launch)
 
     # ---- the step's two kernels one at a time (same arguments as inside the step), K launches each -----
-    pack_ms = time_launches(torch, lambda i: sv.signum_momentum_pack(grads[i % nsets], v, beta, signs), K, warmup=2)
-    vote_ms = time_launches(torch, lambda i: sv.vote_apply(signs, d, x, lr), K, warmup=2)
-    pack_bytes, vote_bytes = (12.0 + 1 / 8) * M * d, (M / 8 + 8.0) * d
+    kernels = None
+    if not args.one_kernel:
+        pack_ms = time_launches(torch, lambda i: sv.signum_momentum_pack(grads[i % nsets], v, beta, signs), K, warmup=2)
+        vote_ms = time_launches(torch, lambda i: sv.vote_apply(signs, d, x, lr), K, warmup=2)
+        pack_bytes, vote_bytes = (12.0 + 1 / 8) * M * d, (M / 8 + 8.0) * d
+        kernels = [
+            {"name": "ssv::pack_rows_kernel (momentum + sign + pack, the dominant kernel)", "ms": pack_ms,
+             "algorithmic_bytes": pack_bytes, "GB/s": pack_bytes / pack_ms / 1e6,
+             "frac": pack_bytes / pack_ms / 1e6 / HBM_PEAK_GBS},
+            {"name": "ssv::vote_apply_kernel (vote + update on the packed rows; what it reads was written just before, "
+                     "so part of it comes from the 256 MB Infinity Cache)", "ms": vote_ms,
+             "algorithmic_bytes": vote_bytes, "GB/s": vote_bytes / vote_ms / 1e6,
+             "frac": vote_bytes / vote_ms / 1e6 / HBM_PEAK_GBS}]
 
     algo_bytes = float(M * 12 + 8) * d
     achieved = algo_bytes / (kern_ms * 1e-3) / 1e9
-    default_workload = (M == 15 and d == RESNET50_D and stride % 32 == 0)
+    default_workload = (M == 15 and d == RESNET50_D and stride % 32 == 0 and not args.one_kernel)
     traffic = read_traffic("signum_step_resnet50_pmc.txt") if default_workload else None
     out = {
         "metric": "voted coords/sec (M*d/s), fused Signum step (momentum + sign + majority vote + update)",
@@ -392,7 +406,8 @@ def main():
         "config": {"workload": "resnet50-sized fused Signum step", "d": d, "M": M, "beta": beta, "lr": lr,
                    "grad_dtype": "f32", "weight_dtype": "f32", "row_stride": stride,
                    "gradient_sets_cycled": nsets,
-                   "kernel": "ssv_signum_step with signs_out = ssv::pack_rows_kernel + ssv::vote_apply_kernel"},
+                   "kernel": ("ssv_signum_step without signs_out = ssv::step_kernel" if args.one_kernel else
+                              "ssv_signum_step with signs_out = ssv::pack_rows_kernel + ssv::vote_apply_kernel")},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic,
@@ -401,16 +416,9 @@ def main():
                                         "measurement, not taken in this run") if traffic else None,
                      "kernel_ms": kern_ms, "algorithmic_bytes_per_launch": algo_bytes,
                      "note": "achieved = bytes the fused step must move (188 B per coordinate: g, v in, v out per worker, "
-                             "x in and out) / HIP-event time of the whole step, both kernels; the packed signs the "
-                             "two-kernel form writes and re-reads (2 x M/8 B per coordinate) are not counted",
-                     "kernels": [
-                         {"name": "ssv::pack_rows_kernel (momentum + sign + pack, the dominant kernel)", "ms": pack_ms,
-                          "algorithmic_bytes": pack_bytes, "GB/s": pack_bytes / pack_ms / 1e6,
-                          "frac": pack_bytes / pack_ms / 1e6 / HBM_PEAK_GBS},
-                         {"name": "ssv::vote_apply_kernel (vote + update on the packed rows; its 150 MB working set "
-                                  "is partly served by the 256 MB Infinity Cache here)", "ms": vote_ms,
-                          "algorithmic_bytes": vote_bytes, "GB/s": vote_bytes / vote_ms / 1e6,
-                          "frac": vote_bytes / vote_ms / 1e6 / HBM_PEAK_GBS}]},
+                             "x in and out) / HIP-event time of the whole step; the packed signs that the two-kernel "
+                             "form writes and re-reads (2 x M/8 B per coordinate) are not counted",
+                     "kernels": kernels},
         "bytes_per_voted_coordinate": {"algorithmic": algo_bytes / d,
                                        "measured_hbm": (traffic / d) if traffic else None},
         "cpu_baseline": cpu,
