@@ -140,6 +140,8 @@ def other_kernels(torch, sv, wl, dev, quick):
     out["signum_step_resnet50_M15_one_kernel_vote_out"] = entry(ms, (12.0 * M + 8 + 1 / 8) * d, launches=1)
     ms = time_launches(torch, lambda i: sv.signum_step(grads[i % 4], None, 0.0, x, 1e-4), n(50), warmup=3)
     out["signsgd_step_resnet50_M15_one_kernel"] = entry(ms, (4.0 * M + 8) * d, launches=1, note="no momentum (beta = 0)")
+    ms = time_launches(torch, lambda i: sv.signum_step(grads[i % 4], None, 0.0, x, 1e-4, signs_out=signs), n(50), warmup=3)
+    out["signsgd_step_resnet50_M15"] = entry(ms, (4.0 * M + 8) * d, launches=2, note="no momentum (beta = 0), with signs_out")
 
     # ---- the step on the natural [M][d] layout (row stride d: rows only 32-byte phased), both forms
     gnat = [wl.worker_gradients(mu, M, s, base_seed=3000, row_stride=d) for s in range(4)]
