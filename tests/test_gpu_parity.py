@@ -336,16 +336,22 @@ def test_step_special_values_do_not_spread(sv):
     x_ref, v_ref = wl.to_numpy(x).copy(), np.zeros((M, d), np.float32)
     vote = torch.empty((sv.words_for(d),), dtype=torch.int64, device=DEV)
     signs = torch.empty((M, sv.words_for(d)), dtype=torch.int64, device=DEV)
+    # the same state through the one-kernel forms (with and without the packed vote as output)
+    x_one, v_one, x_lean, v_lean = x.clone(), v.clone(), x.clone(), v.clone()
+    vote_one = torch.empty_like(vote)
     for _ in range(2):
-        sv.signum_step(g, v, 0.9, x, 1e-3, vote_out=vote, signs_out=signs)
+        sv.signum_step(g, v, 0.9, x, 1e-3, vote_out=vote, signs_out=signs)          # two kernels
+        sv.signum_step(g, v_one, 0.9, x_one, 1e-3, vote_out=vote_one)
+        sv.signum_step(g, v_lean, 0.9, x_lean, 1e-3)
         torch.cuda.synchronize()
         vote_ref, signs_ref = ora.signum_step(wl.to_numpy(g), v_ref, 0.9, x_ref, 1e-3, want_signs=True)
         assert np.array_equal(wl.to_numpy(signs), signs_ref)
-        assert np.array_equal(wl.to_numpy(vote), vote_ref)
-        assert np.array_equal(wl.to_numpy(x), x_ref)
-        v_gpu = wl.to_numpy(v)
+        assert np.array_equal(wl.to_numpy(vote), vote_ref) and torch.equal(vote_one, vote)
+        assert np.array_equal(wl.to_numpy(x), x_ref) and torch.equal(x_one, x) and torch.equal(x_lean, x)
         nan = np.isnan(v_ref)                      # NaN payloads are not compared, NaN-ness is
-        assert np.array_equal(np.isnan(v_gpu), nan) and np.array_equal(v_gpu[~nan], v_ref[~nan])
+        for v_form in (v, v_one, v_lean):
+            v_gpu = wl.to_numpy(v_form)
+            assert np.array_equal(np.isnan(v_gpu), nan) and np.array_equal(v_gpu[~nan], v_ref[~nan])
     assert np.isfinite(wl.to_numpy(x)).all()
 
 
@@ -388,16 +394,20 @@ def test_step_special_values_bf16(sv):
         W = sv.words_for(d)
         vote = torch.empty((W,), dtype=torch.int64, device=DEV)
         signs = torch.empty((M, W), dtype=torch.int64, device=DEV)
+        x_one, v_one, vote_one = _bf16_tensor(x_bits), torch.zeros((M, d), device=DEV), torch.empty_like(vote)
         for step in range(2):
-            sv.signum_step(g, v, 0.9, x, 1e-3, wd, vote_out=vote, signs_out=signs)
+            sv.signum_step(g, v, 0.9, x, 1e-3, wd, vote_out=vote, signs_out=signs)      # two kernels
+            sv.signum_step(g, v_one, 0.9, x_one, 1e-3, wd, vote_out=vote_one)           # one kernel
             torch.cuda.synchronize()
             vote_ref, signs_ref = ora.signum_step(g_bits, v_ref, 0.9, x_ref, 1e-3, wd, want_signs=True)
             assert np.array_equal(wl.to_numpy(signs), signs_ref), f"signs, step {step}"
-            assert np.array_equal(wl.to_numpy(vote), vote_ref), f"vote, step {step}"
+            assert np.array_equal(wl.to_numpy(vote), vote_ref) and torch.equal(vote_one, vote), f"vote, step {step}"
             assert _same_up_to_nan_payload_bf16(wl.to_numpy(x), x_ref), f"weights, step {step}"
-            v_gpu = wl.to_numpy(v)
+            assert _same_up_to_nan_payload_bf16(wl.to_numpy(x_one), x_ref), f"weights of the one-kernel form, step {step}"
             nan = np.isnan(v_ref)
-            assert np.array_equal(np.isnan(v_gpu), nan) and np.array_equal(v_gpu[~nan], v_ref[~nan])
+            for v_form in (v, v_one):
+                v_gpu = wl.to_numpy(v_form)
+                assert np.array_equal(np.isnan(v_gpu), nan) and np.array_equal(v_gpu[~nan], v_ref[~nan])
         # the unfused update from the same vote sees the same special weights
         x2 = _bf16_tensor(x_bits)
         x2_ref = x_bits.copy()
