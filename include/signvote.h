@@ -21,7 +21,8 @@
  *
  * Memory and ownership: every pointer is DEVICE memory owned by the caller unless the argument
  * is documented as host memory.  The library allocates nothing, never frees, and keeps no state
- * between calls apart from one measurement switch read from the environment on first use:
+ * between calls apart from the built-in scratch array of ssv_qsgd_norms_static (signvote_qsgd.h) and one
+ * measurement switch read from the environment on first use:
  *     SSV_TUNE_STEP_SERIAL=0   let the momentum forms of the gradient-side kernels (ssv_signum_step with v,
  *                              ssv_signum_momentum_pack) keep all row loads of a worker group in
  *                              flight instead of one load per wavefront at a time.  Results are
@@ -42,7 +43,7 @@
  * (4 / 2 / 8 bytes), else SSV_ERR_ALIGN.  The fast paths need 16-byte aligned bases and row
  * strides that are multiples of 16 bytes; other shapes take a narrower-load path with the same
  * results.  For full speed start every row on a 128-byte boundary (pad the row strides): a
- * wavefront's 1 KiB accesses then cover whole cache lines (about 10% faster on the fused step).
+ * wavefront's 1 KiB accesses then cover whole cache lines (5-8% faster on the Signum step).
  */
 #ifndef SIGNVOTE_H
 #define SIGNVOTE_H
