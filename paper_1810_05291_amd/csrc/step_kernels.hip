@@ -27,6 +27,8 @@
 
 namespace ssv {
 
+constexpr int64_t kShortVector = int64_t(1) << 21;      // coordinates below which the one-kernel step uses 1 tile per wave
+
 // ---- the one-kernel step --------------------------------------------------------------------------------------
 // Per group of U = 2 workers a wave reads its 2*U*SUB row pieces one at a time (each load waits for the one before),
 // then computes and issues the U*SUB momentum stores back to back: a read phase and a write burst per group.
@@ -47,9 +49,14 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(5, 5))) 
     }
 }
 
-template <typename GT, typename XT, int VEC, bool MOM, bool OUT, bool SERIAL>
+template <typename GT, typename XT, int VEC, bool MOM, bool OUT, bool SERIAL, int SUB = kStepSub>
 static hipError_t launch_out(StepArgs a, hipStream_t s) {
-    constexpr int SUB = kStepSub;
+    // Short vectors: with fewer than about 500 workgroups of 16 tiles the chip is not full and every wave walks a
+    // long chain of dependent loads, so such calls use one tile per wave (four times the workgroups, a quarter of
+    // the chain).  M = 15: d = 2^20 69 -> 33 us, d = 2^16 57 -> 17 us; from d = 2^22 on the 4-tile form is faster.
+    if constexpr (SUB == kStepSub) {
+        if (a.d < kShortVector) return launch_out<GT, XT, VEC, MOM, OUT, SERIAL, 1>(a, s);
+    }
     constexpr int64_t kTile = (int64_t)kWave * VEC;
     constexpr int64_t kBlockTiles = (int64_t)kWavesPerBlock * SUB;
     a.ntiles = (a.d + kTile - 1) / kTile;

@@ -297,7 +297,9 @@ def test_step_tiny_config_signsgd(sv):
 @pytest.mark.parametrize("M,d,pad,x_off", [(1, 1, 0, 0), (2, 64, 0, 0), (3, 257, 0, 0), (15, 100003, 0, 0),
                                             (15, 100003, 1, 0), (15, 100000, 0, 1), (31, 70001, 3, 0),
                                             (16, 4096, 0, 0), (40, 3000, 0, 0), (255, 4097, 0, 0),
-                                            (1023, 2049, 0, 0), (1022, 700, 2, 1)])
+                                            (1023, 2049, 0, 0), (1022, 700, 2, 1),
+                                            # beyond 2^21 coordinates the one-kernel form holds 4 tiles per wave instead of 1
+                                            (3, (1 << 21) + 4099, 0, 0), (5, (1 << 21) + 258, 1, 1)])
 def test_step_signum_fp32(sv, M, d, pad, x_off):
     _log(f"signum_step fp32 M={M} d={d} pad={pad} x_off={x_off}")
     nz = _step_case(sv, M, d, torch.float32, torch.float32, 0.9, 0.0, steps=3, pad=pad, x_off=x_off)
@@ -307,7 +309,7 @@ def test_step_signum_fp32(sv, M, d, pad, x_off):
 
 @pytest.mark.parametrize("g_dtype,x_dtype", [(torch.bfloat16, torch.bfloat16), (torch.bfloat16, torch.float32),
                                               (torch.float32, torch.bfloat16)])
-@pytest.mark.parametrize("M,d,pad", [(31, 100003, 0), (31, 65536 + 8, 0), (5, 999, 5), (3, 8, 0)])
+@pytest.mark.parametrize("M,d,pad", [(31, 100003, 0), (31, 65536 + 8, 0), (5, 999, 5), (3, 8, 0), (3, (1 << 21) + 777, 0)])
 def test_step_signum_mixed_dtypes(sv, M, d, pad, g_dtype, x_dtype):
     _log(f"signum_step M={M} d={d} pad={pad} g={g_dtype} x={x_dtype}")
     assert _step_case(sv, M, d, g_dtype, x_dtype, 0.9, 0.0, steps=2, pad=pad) == 0
@@ -316,6 +318,7 @@ def test_step_signum_mixed_dtypes(sv, M, d, pad, g_dtype, x_dtype):
 def test_step_weight_decay_flip_and_no_momentum(sv):
     flip = [1, 0, 1, 0, 0, 1, 0]
     assert _step_case(sv, 7, 50001, torch.float32, torch.float32, 0.5, 0.01, steps=2, flip=flip) == 0
+    assert _step_case(sv, 7, (1 << 21) + 50001, torch.float32, torch.float32, 0.5, 0.01, steps=2, flip=flip) == 0   # 4 tiles per wave
     assert _step_case(sv, 7, 50001, torch.float32, torch.float32, 0.0, 0.0, steps=1, flip=flip, momentum=False) == 0
     assert _step_case(sv, 6, 3001, torch.bfloat16, torch.bfloat16, 0.0, 0.001, steps=1, momentum=False) == 0
     # beta = 0 with a momentum buffer: v becomes the gradient
