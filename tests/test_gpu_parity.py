@@ -594,6 +594,41 @@ def test_step_multi_equals_flat_step_on_one_large_tensor(sv):
         sv.signum_step_multi(plan_ws, 0.9, 1e-4, workspace=ws[:-1])         # one word short
 
 
+@pytest.mark.parametrize("M", [17, 70, 300])
+def test_step_multi_worker_counts_beyond_15(sv, M):
+    # the vote of the two-kernel multi-tensor form keeps 4 / 6 / 8 / 10 bit planes for M <= 15 / 63 / 255 / 1023:
+    # both multi-tensor forms against the oracle on a few ragged tensors for the larger counters
+    sizes = [1, 65, 4097, 9000, 256, 70_000]
+    beta, lr = 0.9, 1e-4
+    mus = [wl.shared_mean(n, seed=300 + t, device=DEV) for t, n in enumerate(sizes)]
+    grads = [[torch.empty(n, device=DEV) for n in sizes] for _ in range(M)]
+    state = {}
+    for form in ("one", "two"):
+        params = [wl.gaussian((n,), 0.02, seed=400 + t, device=DEV) for t, n in enumerate(sizes)]
+        moms = [[torch.zeros(n, device=DEV) for n in sizes] for _ in range(M)]
+        plan = sv.MultiTensorPlan(params, grads, moms)
+        state[form] = (params, moms, plan, sv.multi_workspace(plan) if form == "two" else None)
+    x_ref = [wl.to_numpy(p).copy() for p in state["one"][0]]
+    v_ref = [np.zeros((M, n), np.float32) for n in sizes]
+    for step in range(2):
+        for t, n in enumerate(sizes):
+            gt = wl.worker_gradients(mus[t], M, step, base_seed=7000 + 13 * t)
+            for m in range(M):
+                grads[m][t].copy_(gt[m])
+        for form in ("one", "two"):
+            _, _, plan, ws = state[form]
+            sv.signum_step_multi(plan, beta, lr, workspace=ws)
+        torch.cuda.synchronize()
+        for t, n in enumerate(sizes):
+            g_h = np.stack([wl.to_numpy(grads[m][t]) for m in range(M)])
+            ora.signum_step(g_h, v_ref[t], beta, x_ref[t], lr)
+            for form in ("one", "two"):
+                params, moms, _, _ = state[form]
+                assert np.array_equal(wl.to_numpy(params[t]), x_ref[t]), f"{form}-kernel form, weights of tensor {t}, step {step}"
+                v_gpu = np.stack([wl.to_numpy(moms[m][t]) for m in range(M)])
+                assert np.array_equal(v_gpu, v_ref[t]), f"{form}-kernel form, momentum of tensor {t}, step {step}"
+
+
 def test_multi_plan_rejects_bad_tensor_lists(sv):
     x = [torch.zeros(10, device=DEV), torch.zeros(20, device=DEV)]
     g = [[torch.zeros(10, device=DEV), torch.zeros(20, device=DEV)] for _ in range(3)]
