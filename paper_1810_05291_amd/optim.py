@@ -47,7 +47,28 @@ class FlatLayout:
         return [flat[o:o + n].view(s) for o, n, s in zip(self.offsets, self.sizes, self.shapes)]
 
 
-class SignumMajorityVote:
+class _GraphedStep:
+    """Optional HIP graph around a driver's step: the library only launches kernels on the caller's stream (no
+    allocation, no memset), so one step can be captured once and replayed.  For small models the two launches of a
+    step cost more on the host than on the GPU; a replay is one host call."""
+
+    _graph = None
+
+    def capture_graph(self):
+        """Capture one step into a HIP graph; from then on step() without arguments replays it.  The buffers the
+        step reads and writes keep their addresses for the life of the driver, so replays see refilled gradients."""
+        dev = self._graph_device()
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream(device=dev)
+        side.wait_stream(torch.cuda.current_stream(dev))
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                self._launch()
+        torch.cuda.current_stream(dev).wait_stream(side)
+        self._graph = graph                                   # capture does not execute: no step has been taken
+
+
+class SignumMajorityVote(_GraphedStep):
     """Signum with majority vote (Algorithm 1) for M simulated workers on one GPU.
 
     params            list of views into the flat weight vector (update happens in place)
@@ -75,9 +96,18 @@ class SignumMajorityVote:
         self.signs = torch.empty((self.M, ((W + 15) // 16) * 16), dtype=torch.int64, device=device)[:, :W]
         self.steps = 0
 
-    def step(self, worker_flip=None, vote_out=None):
+    def _graph_device(self):
+        return self.x.device
+
+    def _launch(self, worker_flip=None, vote_out=None):
         _b.signum_step(self.g, self.v, self.beta, self.x, self.lr, self.weight_decay, vote_out=vote_out,
                        signs_out=self.signs, worker_flip=worker_flip)
+
+    def step(self, worker_flip=None, vote_out=None):
+        if self._graph is not None and worker_flip is None and vote_out is None:
+            self._graph.replay()
+        else:
+            self._launch(worker_flip, vote_out)
         self.steps += 1
 
     def state_dict(self):
@@ -91,7 +121,7 @@ class SignumMajorityVote:
         self.steps = int(state["steps"])
 
 
-class SignumMajorityVoteMulti:
+class SignumMajorityVoteMulti(_GraphedStep):
     """Signum with majority vote (Algorithm 1) on tensors that stay where they are.
 
     params          list of T weight tensors on the GPU (updated in place)
@@ -119,6 +149,15 @@ class SignumMajorityVoteMulti:
         self.workspace = _b.multi_workspace(self.plan)      # the workers' packed signs: selects the two-kernel form
         self.steps = 0
 
-    def step(self):
+    def _graph_device(self):
+        return self.params[0].device
+
+    def _launch(self):
         _b.signum_step_multi(self.plan, self.beta, self.lr, self.weight_decay, workspace=self.workspace)
+
+    def step(self):
+        if self._graph is not None:
+            self._graph.replay()
+        else:
+            self._launch()
         self.steps += 1

@@ -234,6 +234,50 @@ def test_small_model_trains_through_the_flat_layout(sv):
     assert torch.equal(opt.x, after)
 
 
+@pytest.mark.parametrize("driver", ["flat", "multi"])
+def test_drivers_replay_their_step_as_a_hip_graph(sv, driver):
+    # capture_graph() records one step (two kernel launches) once; every later step() is a replay.  Replays are
+    # interleaved with eager work and synchronisations and compared with an eager twin and with the oracle.
+    M, steps = 4, 6
+    shapes = [(33, 7), (33,), (5000,), (1,)]
+    sizes = [int(np.prod(s)) for s in shapes]
+    if driver == "flat":
+        make = lambda: sv.SignumMajorityVote(shapes, M, lr=1e-3, beta=0.9, device=DEV)
+        graphed, eager = make(), make()
+        grads_of = lambda o: o.grads
+        weights_of = lambda o: [p.reshape(-1) for p in o.params]
+    else:
+        def make():
+            params = [torch.zeros(s, device=DEV) for s in shapes]
+            wg = [[torch.zeros(s, device=DEV) for s in shapes] for _ in range(M)]
+            return sv.SignumMajorityVoteMulti(params, wg, lr=1e-3, beta=0.9)
+        graphed, eager = make(), make()
+        grads_of = lambda o: o.worker_grads
+        weights_of = lambda o: [p.reshape(-1) for p in o.params]
+    for o in (graphed, eager):
+        for t, w in enumerate(weights_of(o)):
+            w.copy_(wl.gaussian((sizes[t],), 0.02, seed=50 + t, device=DEV))
+    x_ref = [_host(w).copy() for w in weights_of(eager)]
+    v_ref = [np.zeros((M, n), np.float32) for n in sizes]
+    graphed.capture_graph()
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(weights_of(graphed), weights_of(eager))), "capture must not execute"
+    for k in range(steps):
+        for t, n in enumerate(sizes):
+            gt = wl.gaussian((M, n), 1e-2, seed=900 + 10 * k + t, device=DEV)
+            for o in (graphed, eager):
+                for m in range(M):
+                    grads_of(o)[m][t].reshape(-1).copy_(gt[m])
+            ora.signum_step(_host(gt), v_ref[t], 0.9, x_ref[t], 1e-3)
+        graphed.step()                                          # replay
+        eager.step()                                            # eager launches between the replays
+        torch.cuda.synchronize()
+        for t in range(len(sizes)):
+            assert torch.equal(weights_of(graphed)[t], weights_of(eager)[t]), f"replay {k}, tensor {t}"
+            assert np.array_equal(_host(weights_of(graphed)[t]), x_ref[t]), f"replay {k}, tensor {t} vs the oracle"
+    assert graphed.steps == steps
+
+
 def test_small_model_trains_with_gradients_left_where_autograd_put_them(sv):
     # the same two-layer network, but every worker's gradients stay in the tensors autograd wrote them to; the
     # multi-tensor step takes them from there (no copy into a flat buffer), one launch per step
