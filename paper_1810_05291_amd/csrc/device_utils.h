@@ -153,17 +153,14 @@ __device__ __forceinline__ uint32_t dpp_or(uint32_t v) {
     return v | (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
 }
 
-// NT: store with the non-temporal hint.  It pays where the packed words are the kernel's only output (the sign-only
-// form: +1-4%), and costs 0.5-2% where they accompany a momentum or bit-plane write stream, which keeps plain stores.
-template <int VEC, bool NT = false>
+// Plain stores on purpose: with the non-temporal hint these 32-byte pieces reach memory as partial-line writes (the
+// sign-only form then writes 1.21 x its packed bytes) and the momentum and bit-plane kernels run 0.5-2% slower.
+template <int VEC>
 __device__ __forceinline__ void pack_store_tile(uint64_t* __restrict__ row, int64_t tile, int64_t W, int lane,
                                                 const uint32_t (&b)[VEC]) {
     if constexpr (VEC == 1) {
         const uint64_t word = __ballot(b[0] != 0);
-        if (lane == 0 && tile < W) {
-            if constexpr (NT) stream_store(row + tile, word);
-            else row[tile] = word;
-        }
+        if (lane == 0 && tile < W) row[tile] = word;
     } else {
         static_assert(VEC == 4, "1 or 4 coordinates per lane");
         uint32_t v = (b[0] | (b[1] << 1) | (b[2] << 2) | (b[3] << 3)) << (4 * (lane & 7));
@@ -171,10 +168,7 @@ __device__ __forceinline__ void pack_store_tile(uint64_t* __restrict__ row, int6
         v = dpp_or<0x4E>(v);     // quad_perm [2,3,0,1]
         v = dpp_or<0x141>(v);    // row_half_mirror
         const int64_t dw = tile * 8 + (lane >> 3);          // dword index inside the packed row
-        if ((lane & 7) == 0 && (dw >> 1) < W) {
-            if constexpr (NT) stream_store(reinterpret_cast<uint32_t*>(row) + dw, v);
-            else reinterpret_cast<uint32_t*>(row)[dw] = v;
-        }
+        if ((lane & 7) == 0 && (dw >> 1) < W) reinterpret_cast<uint32_t*>(row)[dw] = v;
     }
 }
 

@@ -114,7 +114,7 @@ __device__ __forceinline__ void worker_group(const StepArgs& a, const RowStarts<
                 cnt[s][c >> 1] += b[c] << (16 * (c & 1));      // two 16-bit counters per register (M <= 1023)
             }
             if (OUT && a.signs_out != nullptr)
-                pack_store_tile<VEC, !MOM>(a.signs_out + (int64_t)m * a.signs_stride, tile0 + s * kWavesPerBlock, a.W, lane, b);
+                pack_store_tile<VEC>(a.signs_out + (int64_t)m * a.signs_stride, tile0 + s * kWavesPerBlock, a.W, lane, b);
         }
     }
 }

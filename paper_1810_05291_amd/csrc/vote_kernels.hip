@@ -67,7 +67,7 @@ __device__ __forceinline__ void vote_tile(const VoteArgs& a, int64_t dw0, int nv
             vt[q] = pl[NPL - 1][q] & mask;
         }
         // Non-temporal like the loads: with plain stores the vote's output, 0.4% of its traffic, costs the d = 2^30,
-        // M = 255 vote 4-5% of its time (5.47 -> 5.20 ms); with no stores at all it would take 4.90 ms.
+        // M = 255 vote 4-5% of its time (5.47-5.63 -> 5.18-5.38 ms); with no stores at all it would take 4.90 ms.
         uint32_t* o = reinterpret_cast<uint32_t*>(a.vote_out) + dw0;
         if constexpr (PW == 4) {
             if (FULL || nv == 4) {
