@@ -172,25 +172,4 @@ __device__ __forceinline__ void pack_store_tile(uint64_t* __restrict__ row, int6
     }
 }
 
-// Four ADJACENT tiles of one wave (VEC = 4): the 32 dwords they pack to are one 128-byte line of the row, written with
-// ONE non-temporal store instruction (lane 8 q + s, s < 4, stores dword q of tile s).  For the sign-only kernel, whose
-// packed words are its only output, this measures 2.5% faster than four plain 32-byte pieces per wave (resnet50 size,
-// M = 15: 0.251 -> 0.244 ms); a full line with plain stores gains nothing, non-temporal 32-byte pieces reach memory as
-// partial-line writes.
-__device__ __forceinline__ void pack_store_four_tiles(uint64_t* __restrict__ row, int64_t tile0, int64_t W, int lane,
-                                                      const uint32_t (&b)[4][4]) {
-    uint32_t merged[4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        uint32_t v = (b[s][0] | (b[s][1] << 1) | (b[s][2] << 2) | (b[s][3] << 3)) << (4 * (lane & 7));
-        v = dpp_or<0xB1>(v);     // quad_perm [1,0,3,2]
-        v = dpp_or<0x4E>(v);     // quad_perm [2,3,0,1]
-        merged[s] = dpp_or<0x141>(v);    // row_half_mirror: every lane of a group of 8 now holds the group's dword
-    }
-    const int s = lane & 7;
-    const uint32_t mine = s == 0 ? merged[0] : (s == 1 ? merged[1] : (s == 2 ? merged[2] : merged[3]));
-    const int64_t dw = (tile0 + s) * 8 + (lane >> 3);
-    if (s < 4 && (dw >> 1) < W) stream_store(reinterpret_cast<uint32_t*>(row) + dw, mine);
-}
-
 }  // namespace ssv

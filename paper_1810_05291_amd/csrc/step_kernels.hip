@@ -80,8 +80,7 @@ static hipError_t launch_out(StepArgs a, hipStream_t s) {
 // row (a persistent grid): every stream then has as many scattered access points as there are workgroups (66%).
 //   momentum form: SUB = 1, one row load in flight per wave (load g, load v, store v: SUB = 2 / 4 / 8 measured
 //                  79 / 75 / 72%), as many waves per SIMD as fit (capping them at 5 costs 17 points);
-//   sign-only form: SUB = 4 with all loads in flight (SUB = 1 / 2 / 8: 72 / 75 / 77%); at four coordinates per lane
-//                  it has a kernel of its own, sign_rows_kernel, and this one serves the one-coordinate-per-lane path.
+//   sign-only form: SUB = 4 with all loads in flight (SUB = 1 / 2 / 8: 72 / 75 / 77%).
 // The rows' ragged ends are taken by the workgroups behind the first nfat of each row, tile by tile with bounds checks.
 template <typename GT, int VEC, int SUB, bool MOM, bool SERIAL>
 __global__ __launch_bounds__(kBlock) void pack_rows_kernel(StepArgs a, int64_t nfat) {
@@ -131,56 +130,6 @@ static hipError_t launch_pack_rows(StepArgs a, hipStream_t s) {
     return hipGetLastError();
 }
 
-// Sign-only form at four coordinates per lane (ssv_sign_pack; first half of a signSGD step with signs_out): a wave
-// takes FOUR ADJACENT tiles, all four loads in flight, and writes their 128 bytes of packed signs with one store
-// (see pack_store_four_tiles).  A workgroup covers 16 tiles of one row; ragged ends as in pack_rows_kernel.
-template <typename GT>
-__global__ __launch_bounds__(kBlock) void sign_rows_kernel(StepArgs a, int64_t nfat) {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);      // tell the compiler it is wave-uniform
-    const int m = blockIdx.y;
-    const int64_t lb = blockIdx.x;
-    constexpr int64_t kTileCoords = (int64_t)kWave * 4;
-    const GT* __restrict__ grow = FlatRows::g<GT>(a, m);
-    uint64_t* srow = a.signs_out + (int64_t)m * a.signs_stride;
-    const uint32_t jl = (uint32_t)lane * 4;
-    if (lb < nfat) {
-        const int64_t tile0 = lb * 16 + wave * 4;
-        float gv[4][4];
-#pragma unroll
-        for (int s = 0; s < 4; ++s) load_vals<4>((grow + (tile0 + s) * kTileCoords) + jl, gv[s]);
-        const uint32_t flip = a.has_flip ? ((a.flip.w[m >> 5] >> (m & 31)) & 1u) : 0u;
-        uint32_t b[4][4];
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-#pragma unroll
-            for (int c = 0; c < 4; ++c) b[s][c] = (gv[s][c] >= 0.0f ? 1u : 0u) ^ flip;
-        pack_store_four_tiles(srow, tile0, a.W, lane, b);
-    } else {
-        const int64_t tile = nfat * 16 + (lb - nfat) * kWavesPerBlock + wave;
-        if (tile < a.ntiles) {                                     // wave-uniform
-            const RowStarts<GT, 1> row = fetch_rows<GT, false, FlatRows, 1>(a, m);
-            const int64_t left = a.d - (tile * kTileCoords + jl);
-            int nvalid[1] = {left >= 4 ? 4 : (left > 0 ? (int)left : 0)};
-            uint32_t unused_count[1][2] = {};
-            worker_group<GT, 4, 1, false, true, true, false, 1>(a, row, m, tile * kTileCoords, jl, nvalid, lane, tile, unused_count);
-        }
-    }
-}
-
-template <typename GT>
-static hipError_t launch_sign_rows(StepArgs a, hipStream_t s) {
-    constexpr int64_t kTile = (int64_t)kWave * 4;
-    a.ntiles = (a.d + kTile - 1) / kTile;
-    const int64_t nfat = (a.d / kTile) / 16;
-    const int64_t tail_tiles = a.ntiles - nfat * 16;
-    const int64_t grid = nfat + (tail_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
-    if (grid > 0x7fffffffLL || a.M > 65535) return hipErrorInvalidConfiguration;
-    (void)hipGetLastError();                 // a stale error of an earlier, unrelated call is not this launch's
-    hipLaunchKernelGGL((sign_rows_kernel<GT>), dim3((unsigned)grid, (unsigned)a.M), dim3(kBlock), 0, s, a, nfat);
-    return hipGetLastError();
-}
-
 template <typename GT, int VEC>
 static hipError_t launch_pack(const StepArgs& a, hipStream_t s) {
     if (a.v != nullptr) {
@@ -188,8 +137,7 @@ static hipError_t launch_pack(const StepArgs& a, hipStream_t s) {
         return tuning().step_serial ? launch_pack_rows<GT, VEC, 1, true, true>(a, s)
                                     : launch_pack_rows<GT, VEC, 1, true, false>(a, s);
     }
-    if constexpr (VEC == 4) return launch_sign_rows<GT>(a, s);
-    else return launch_pack_rows<GT, VEC, 4, false, false>(a, s);
+    return launch_pack_rows<GT, VEC, 4, false, false>(a, s);
 }
 
 template <typename GT, typename XT, int VEC, bool MOM, bool OUT>
